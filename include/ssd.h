@@ -1,0 +1,144 @@
+/*
+ * ssd.h -- C ABI of the gate -> verify -> accept hot path of CTC-draft self-speculative
+ * decoding for speech-aware LLMs, hand-written for AMD gfx950 (MI355X).
+ *
+ * The three compute calls follow the paper's statement of the method:
+ *   ctc_gate        Sec. 2.1: greedy CTC path (Eq. 2), collapse map B, frame-entropy gate (Eq. 3)
+ *   verify_forward  Sec. 2.2: one causal decoder forward over [speech emb g; prompt; draft] (Eq. 4)
+ *   accept_prefix   Sec. 2.2-2.3: draft-token log-likelihoods, relaxed acceptance (Eq. 5) and the
+ *                   longest verified prefix that auto-regressive fallback resumes from (Eq. 7)
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library keeps no caller pointer after a call returns, except the weight
+ *     pointers given to ssd_create, which must stay valid until ssd_destroy.
+ *   - cu_* arrays are HOST arrays of B+1 exclusive prefix sums with cu[0] = 0 (ragged batches are
+ *     host-side knowledge of whoever batches the utterances).  They are read before the call returns.
+ *   - Every call enqueues its work on the hipStream_t given to ssd_create and returns without
+ *     waiting for the device.  Outputs are valid after the caller synchronises that stream.
+ *   - Return value: SSD_OK or a negative ssd_status.  Argument errors are detected on the host
+ *     before anything is launched, so on a non-zero return no output buffer has been written.
+ *     ssd_last_error gives a message for the last failing call on that context.
+ *   - Device memory is allocated only by ssd_create (re-laid-out weights, small tables) and freed by
+ *     ssd_destroy.  All activations live in the caller-provided workspace (ssd_set_workspace).
+ *   - One context must not be used from two host threads at once.
+ */
+#ifndef SSD_H
+#define SSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ssd_ctx ssd_ctx;
+
+enum ssd_status {
+    SSD_OK = 0,
+    SSD_EINVAL = -1,        /* NULL pointer, negative count, malformed cu_* array, id out of range   */
+    SSD_ESHAPE = -2,        /* a size the kernels do not support (see each call)                     */
+    SSD_EWORKSPACE = -3,    /* no workspace set, or it is smaller than ssd_workspace_bytes says      */
+    SSD_EHIP = -4,          /* a HIP runtime call failed (message holds the HIP error string)        */
+    SSD_EUNSUPPORTED = -5   /* dtype / feature not built                                             */
+};
+
+enum ssd_dtype { SSD_F32 = 0, SSD_BF16 = 1 };
+
+/* Decoder-only LLM: pre-norm RMSNorm, grouped-query causal attention with half-split rotary
+ * embedding (component i paired with i + head_dim/2), SwiGLU MLP, no biases.
+ * dtype is the storage type of every weight and of speech_emb.  SSD_F32 is all fp32.  SSD_BF16
+ * runs the contractions on the 16-bit matrix cores with fp32 accumulation and an fp32 residual
+ * stream; the matrix-core operand type is IEEE half: activations are rounded to half (11
+ * significant bits instead of bf16's 8, same MFMA rate) and the bf16 weights are converted once,
+ * exactly, to half times a per-tensor power of two.  Activations beyond the half range (|v| >
+ * 65504 after RMSNorm or in the MLP) are not supported.
+ * Supported: head_dim 128 (bf16) or any multiple of 4 up to 128 (f32); n_q_heads a multiple of
+ * n_kv_heads; for bf16 d_model, d_ff, n_q_heads*head_dim, n_kv_heads*head_dim and vocab multiples
+ * of 128; for f32 d_model, d_ff, n_q_heads*head_dim multiples of 16 and d_model <= 1024. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+    float   rms_eps, rope_theta;
+    int32_t dtype;            /* enum ssd_dtype */
+    int32_t max_positions;    /* longest sequence (speech + prompt + draft rows of one utterance) */
+} ssd_model_cfg;
+
+/* All matrices are row-major [out_features, in_features] (y = W x); per-layer members are HOST
+ * arrays of n_layers DEVICE pointers.  lm_head may alias embed. */
+typedef struct {
+    const void *embed;                /* dev [vocab, d_model]                        */
+    const void *const *wq;            /* dev [n_q_heads*head_dim, d_model] per layer */
+    const void *const *wk;            /* dev [n_kv_heads*head_dim, d_model]          */
+    const void *const *wv;            /* dev [n_kv_heads*head_dim, d_model]          */
+    const void *const *wo;            /* dev [d_model, n_q_heads*head_dim]           */
+    const void *const *w_gate;        /* dev [d_ff, d_model]                         */
+    const void *const *w_up;          /* dev [d_ff, d_model]                         */
+    const void *const *w_down;        /* dev [d_model, d_ff]                         */
+    const void *const *norm_attn;     /* dev [d_model] RMSNorm gain before attention */
+    const void *const *norm_mlp;      /* dev [d_model] RMSNorm gain before the MLP   */
+    const void *norm_final;           /* dev [d_model]                               */
+    const void *lm_head;              /* dev [vocab, d_model]                        */
+} ssd_weights;
+
+/* Create a context bound to `hip_stream` (a hipStream_t, NULL = default stream) on the current
+ * device.  cfg and weights may both be NULL for a context that only runs ctc_gate.  With a model,
+ * the projection weights are copied into library-owned layouts (fused QKV and gate/up; for
+ * SSD_BF16 every matrix incl. lm_head as scaled half), which waits for the copies; embed, the
+ * norm gains (and for SSD_F32 wo, w_down, lm_head) are read in place on every call. */
+int ssd_create(ssd_ctx **out, const ssd_model_cfg *cfg, const ssd_weights *weights, void *hip_stream);
+void ssd_destroy(ssd_ctx *ctx);
+
+/* Bytes of workspace needed for calls with at most max_frames CTC frames, max_tokens decoder rows
+ * (sum over utterances of speech + prompt + draft), max_verify_rows draft tokens and max_utts
+ * utterances.  The workspace is a dev buffer, 256-byte aligned, handed over with
+ * ssd_set_workspace and owned by the caller; it may be replaced between calls. */
+size_t ssd_workspace_bytes(const ssd_ctx *ctx, int64_t max_frames, int64_t max_tokens,
+                           int64_t max_verify_rows, int64_t max_utts);
+int ssd_set_workspace(ssd_ctx *ctx, void *dev_ptr, size_t bytes);
+
+const char *ssd_last_error(const ssd_ctx *ctx);
+
+/* Sec. 2.1.  For every frame t of every utterance: softmax over the V_ctc scores (blank included),
+ * entropy H_t in nats (Eq. 3, left side) and greedy label a_t = lowest-index argmax of the stored
+ * scores (Eq. 2).  Per utterance b (frames cu_frames[b] .. cu_frames[b+1]-1, at least one):
+ *   draft  = B(a): merge consecutive duplicates, then drop blank_id; written to
+ *            draft_ctc[cu_frames[b] ...], its length to draft_len[b];
+ *   max_entropy[b] = max_t H_t;  gate_pass[b] = 1 iff max_entropy[b] < tau_ctc (strict, Eq. 3).
+ * logits: dev [cu_frames[B], V_ctc] packed rows, row-major, dtype SSD_F32 or SSD_BF16; -inf is a
+ * legal score (probability 0), NaN/+inf give unspecified results.
+ * frame_entropy / frame_argmax: optional dev outputs [cu_frames[B]] (NULL to skip). */
+int ctc_gate(ssd_ctx *ctx, const void *logits, int dtype, const int32_t *cu_frames /*host*/, int B,
+             int V_ctc, int blank_id, float tau_ctc,
+             float *frame_entropy, int32_t *frame_argmax,
+             float *max_entropy /*dev [B]*/, uint8_t *gate_pass /*dev [B]*/,
+             int32_t *draft_ctc /*dev [cu_frames[B]]*/, int32_t *draft_len /*dev [B]*/);
+
+/* Sec. 2.2 (Eq. 4; parallel scoring through the causal mask).  For each of the Bv utterances that
+ * did not pass the gate, runs the decoder over the rows [speech_emb rows; embed[prompt ids];
+ * embed[draft ids]] at positions 0..n-1 and writes, for draft token i = 1..U, the final-RMSNormed
+ * hidden row of sequence index S + P + i - 2 (the position whose next-token distribution scores
+ * token i) to h_verify row cu_draft[b] + i - 1.  An utterance needs S + P >= 1; U = 0 is legal.
+ * speech_emb: dev [cu_speech[Bv], d_model]; prompt_ids / draft_ids: dev int32 LLM token ids
+ * (ids outside [0, vocab) are clamped on the device); h_verify: dev [cu_draft[Bv], d_model], IEEE half
+ * for SSD_BF16 models and fp32 for SSD_F32: an activation buffer that accept_prefix consumes. */
+int verify_forward(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_speech /*host*/,
+                   const int32_t *prompt_ids, const int32_t *cu_prompt /*host*/,
+                   const int32_t *draft_ids, const int32_t *cu_draft /*host*/, int Bv,
+                   void *h_verify);
+
+/* Sec. 2.2-2.3 (Eq. 5, definition of j, Eq. 7).  draft_logp[r] = log softmax(lm_head . h_verify[r])
+ * at token draft_ids[r]; the logits are never written to memory.  Token i passes iff
+ * draft_logp > ln(tau_slm), evaluated in fp32 with ln(tau_slm) rounded from double (tau_slm <= 0
+ * accepts everything).  accept_len[b] = j - 1 where j is the first failing token, or U if none;
+ * all_accepted[b] = (accept_len[b] == U).  greedy_tok (optional, NULL to skip) receives the
+ * lowest-index argmax over the vocabulary at every row: the token greedy decoding would emit there. */
+int accept_prefix(ssd_ctx *ctx, const void *h_verify, const int32_t *draft_ids /*dev*/,
+                  const int32_t *cu_draft /*host*/, int Bv, float tau_slm,
+                  float *draft_logp /*dev [cu_draft[Bv]]*/, int32_t *accept_len /*dev [Bv]*/,
+                  uint8_t *all_accepted /*dev [Bv]*/, int32_t *greedy_tok /*dev [cu_draft[Bv]] or NULL*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_H */

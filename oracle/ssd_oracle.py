@@ -157,7 +157,7 @@ def _f64(t) -> np.ndarray:
     """Exact widening of a stored tensor (numpy array or torch tensor, any float type)."""
     if isinstance(t, np.ndarray):
         return t.astype(np.float64)
-    return t.detach().to("cpu").double().numpy()
+    return t.detach().double().cpu().numpy()      # widen where the tensor lives, then copy
 
 
 def decoder_hidden(xs: List[np.ndarray], weights: Dict, cfg) -> List[np.ndarray]:

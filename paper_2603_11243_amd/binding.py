@@ -1,0 +1,208 @@
+"""ctypes binding of the C ABI in include/ssd.h: argument marshalling only.
+
+Torch is used for device memory (tensors own the buffers, `data_ptr()` is what crosses the ABI)
+and for the stream handle.  Every computation happens inside libssd.so.
+"""
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libssd.so")
+
+SSD_F32, SSD_BF16 = 0, 1
+_DTYPE_CODE = {torch.float32: SSD_F32, torch.bfloat16: SSD_BF16}
+_STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE", -4: "SSD_EHIP",
+           -5: "SSD_EUNSUPPORTED"}
+
+EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
+           "ctc_gate", "verify_forward", "accept_prefix"]
+
+
+class SsdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{_STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class ModelCfgC(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
+                ("max_positions", C.c_int32)]
+
+
+class WeightsC(C.Structure):
+    _fields_ = [("embed", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down",
+                                                      "norm_attn", "norm_mlp")] + \
+               [("norm_final", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+def load_library() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2603_11243_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
+    lib.ssd_create.argtypes = [C.POINTER(vp), C.POINTER(ModelCfgC), C.POINTER(WeightsC), vp]
+    lib.ssd_create.restype = i32
+    lib.ssd_destroy.argtypes = [vp]
+    lib.ssd_destroy.restype = None
+    lib.ssd_workspace_bytes.argtypes = [vp, i64, i64, i64, i64]
+    lib.ssd_workspace_bytes.restype = C.c_size_t
+    lib.ssd_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    lib.ssd_set_workspace.restype = i32
+    lib.ssd_last_error.argtypes = [vp]
+    lib.ssd_last_error.restype = C.c_char_p
+    lib.ctc_gate.argtypes = [vp, vp, i32, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
+    lib.ctc_gate.restype = i32
+    lib.verify_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.verify_forward.restype = i32
+    lib.accept_prefix.argtypes = [vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
+    lib.accept_prefix.restype = i32
+    return lib
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_i32(a: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Context:
+    """Owns one ssd_ctx.  `weights` is the dict layout of workloads.make_model_weights (device tensors)."""
+
+    def __init__(self, model_cfg=None, weights: Optional[dict] = None, device="cuda:0", stream=None,
+                 max_positions: int = 1024):
+        self._lib = lib()
+        self.device = torch.device(device)
+        self.cfg = model_cfg
+        self._keep = []               # tensors whose storage the library reads in place
+        self._ws = None
+        self._h = C.c_void_p()
+        torch.cuda.set_device(self.device)
+        st = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.stream = st
+        cfg_p, w_p = None, None
+        if model_cfg is not None:
+            m = model_cfg
+            self.dtype = {"bf16": torch.bfloat16, "f32": torch.float32}[m.dtype]
+            # h_verify is an activation buffer between verify_forward and accept_prefix: IEEE half for
+            # bf16-stored models (the MFMA operand type), fp32 otherwise
+            self.act_dtype = {"bf16": torch.float16, "f32": torch.float32}[m.dtype]
+            cfg_c = ModelCfgC(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ff, m.vocab,
+                              m.rms_eps, m.rope_theta, _DTYPE_CODE[self.dtype], max_positions)
+            w_c = WeightsC()
+
+            def dev(t):
+                t = t.to(self.device).contiguous()
+                assert t.dtype == self.dtype
+                self._keep.append(t)
+                return t.data_ptr()
+
+            w_c.embed = dev(weights["embed"])
+            w_c.lm_head = dev(weights["lm_head"])
+            w_c.norm_final = dev(weights["norm_final"])
+            arrays = []
+            for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_mlp"):
+                arr = (C.c_void_p * m.n_layers)(*[dev(L[name]) for L in weights["layers"]])
+                arrays.append(arr)
+                setattr(w_c, name, C.cast(arr, C.POINTER(C.c_void_p)))
+            cfg_p, w_p = C.byref(cfg_c), C.byref(w_c)
+        rc = self._lib.ssd_create(C.byref(self._h), cfg_p, w_p, C.c_void_p(st.cuda_stream))
+        if rc != 0:
+            raise SsdError(rc, "ssd_create failed")
+
+    def close(self):
+        if self._h:
+            self._lib.ssd_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != 0:
+            raise SsdError(rc, self._lib.ssd_last_error(self._h).decode())
+
+    def workspace_bytes(self, max_frames=0, max_tokens=0, max_verify_rows=0, max_utts=0) -> int:
+        return int(self._lib.ssd_workspace_bytes(self._h, max_frames, max_tokens, max_verify_rows, max_utts))
+
+    def reserve(self, max_frames=0, max_tokens=0, max_verify_rows=0, max_utts=0):
+        """Allocates (through torch) and hands over a workspace big enough for the given maxima."""
+        n = self.workspace_bytes(max_frames, max_tokens, max_verify_rows, max_utts)
+        if self._ws is None or self._ws.numel() < n:
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.device)
+            self._check(self._lib.ssd_set_workspace(self._h, _ptr(self._ws), n))
+
+    def set_workspace(self, buf: Optional[torch.Tensor]):
+        self._ws = buf
+        self._check(self._lib.ssd_set_workspace(self._h, _ptr(buf), 0 if buf is None else buf.numel()))
+
+    # ---- the three calls -------------------------------------------------------------------
+
+    def ctc_gate(self, logits: torch.Tensor, cu_frames, blank_id: int, tau_ctc: float,
+                 want_frames: bool = False, out: Optional[dict] = None) -> dict:
+        cu = _host_i32(cu_frames)
+        B, n_rows, V = len(cu) - 1, int(logits.shape[0]), int(logits.shape[1])
+        dev = self.device
+        if out is None:
+            out = {"max_entropy": torch.empty(max(B, 0), dtype=torch.float32, device=dev),
+                   "gate_pass": torch.empty(max(B, 0), dtype=torch.uint8, device=dev),
+                   "draft_ctc": torch.empty(n_rows, dtype=torch.int32, device=dev),
+                   "draft_len": torch.empty(max(B, 0), dtype=torch.int32, device=dev)}
+            if want_frames:
+                out["frame_entropy"] = torch.empty(n_rows, dtype=torch.float32, device=dev)
+                out["frame_argmax"] = torch.empty(n_rows, dtype=torch.int32, device=dev)
+        self._check(self._lib.ctc_gate(self._h, _ptr(logits), _DTYPE_CODE[logits.dtype], cu.ctypes.data, B, V,
+                                       blank_id, tau_ctc, _ptr(out.get("frame_entropy")),
+                                       _ptr(out.get("frame_argmax")), _ptr(out["max_entropy"]),
+                                       _ptr(out["gate_pass"]), _ptr(out["draft_ctc"]), _ptr(out["draft_len"])))
+        return out
+
+    def verify_forward(self, speech_emb: torch.Tensor, cu_speech, prompt_ids: torch.Tensor, cu_prompt,
+                       draft_ids: torch.Tensor, cu_draft, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        cs, cp, cd = _host_i32(cu_speech), _host_i32(cu_prompt), _host_i32(cu_draft)
+        Bv = len(cd) - 1
+        if out is None:
+            out = torch.empty((int(cd[-1]), self.cfg.d_model), dtype=self.act_dtype, device=self.device)
+        self._check(self._lib.verify_forward(self._h, _ptr(speech_emb), cs.ctypes.data, _ptr(prompt_ids),
+                                             cp.ctypes.data, _ptr(draft_ids), cd.ctypes.data, Bv, _ptr(out)))
+        return out
+
+    def accept_prefix(self, h_verify: torch.Tensor, draft_ids: torch.Tensor, cu_draft, tau_slm: float,
+                      want_greedy: bool = False, out: Optional[dict] = None) -> dict:
+        cd = _host_i32(cu_draft)
+        Bv, Mv = len(cd) - 1, int(cd[-1])
+        dev = self.device
+        if out is None:
+            out = {"draft_logp": torch.empty(Mv, dtype=torch.float32, device=dev),
+                   "accept_len": torch.empty(max(Bv, 0), dtype=torch.int32, device=dev),
+                   "all_accepted": torch.empty(max(Bv, 0), dtype=torch.uint8, device=dev)}
+            if want_greedy:
+                out["greedy_tok"] = torch.empty(Mv, dtype=torch.int32, device=dev)
+        self._check(self._lib.accept_prefix(self._h, _ptr(h_verify), _ptr(draft_ids), cd.ctypes.data, Bv, tau_slm,
+                                            _ptr(out["draft_logp"]), _ptr(out["accept_len"]),
+                                            _ptr(out["all_accepted"]), _ptr(out.get("greedy_tok"))))
+        return out

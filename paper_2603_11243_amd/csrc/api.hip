@@ -1,0 +1,488 @@
+// C-ABI layer: argument checks, host-side ragged-batch metadata, workspace carving, launches.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "ssd_internal.h"
+
+using namespace ssd;
+
+namespace {
+
+// Pinned host staging for per-call metadata.  A ring of slots, each guarded by an event recorded
+// after its upload, lets back-to-back calls proceed without waiting for the device.
+struct Stager {
+    static constexpr int SLOTS = 8;
+    void* buf[SLOTS] = {};
+    size_t cap[SLOTS] = {};
+    hipEvent_t ev[SLOTS] = {};
+    bool used[SLOTS] = {};
+    int next = 0;
+    hipError_t acquire(size_t bytes, int& slot, void*& p) {
+        slot = next;
+        next = (next + 1) % SLOTS;
+        hipError_t e;
+        if (!ev[slot] && (e = hipEventCreateWithFlags(&ev[slot], hipEventDisableTiming)) != hipSuccess) return e;
+        if (used[slot] && (e = hipEventSynchronize(ev[slot])) != hipSuccess) return e;
+        if (cap[slot] < bytes) {
+            if (buf[slot]) (void)hipHostFree(buf[slot]);
+            buf[slot] = nullptr;
+            cap[slot] = 0;
+            const size_t want = std::max<size_t>(bytes * 2, 4096);
+            if ((e = hipHostMalloc(&buf[slot], want, hipHostMallocDefault)) != hipSuccess) return e;
+            cap[slot] = want;
+        }
+        p = buf[slot];
+        return hipSuccess;
+    }
+    hipError_t commit(int slot, hipStream_t st) {
+        used[slot] = true;
+        return hipEventRecord(ev[slot], st);
+    }
+    void release() {
+        for (int i = 0; i < SLOTS; ++i) {
+            if (buf[i]) (void)hipHostFree(buf[i]);
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+            buf[i] = nullptr; ev[i] = nullptr; cap[i] = 0; used[i] = false;
+        }
+    }
+};
+
+}  // namespace
+
+struct ssd_ctx {
+    hipStream_t stream = nullptr;
+    bool has_model = false;
+    ssd_model_cfg cfg{};
+    const void* embed = nullptr;
+    const void* lm_head = nullptr;
+    const void* norm_final = nullptr;
+    std::vector<const void*> wo, w_down, norm_attn, norm_mlp;   // wo / w_down: what the GEMMs read
+    std::vector<void*> wqkv, wgu;            // library-owned fused layouts
+    std::vector<void*> owned;                // every device allocation made by ssd_create
+    // bf16 models: weights live as f16 * 2^k; these undo the scale in the GEMM epilogues
+    std::vector<float> ds_qkv, ds_o, ds_gu, ds_down;
+    float ds_lm = 1.f;
+    float* rope_tab = nullptr;               // [max_positions][head_dim/2] (cos, sin) pairs
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    std::string err;
+    Stager stager;
+};
+
+namespace {
+
+int fail(ssd_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, expr)                                                                          \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) return fail((c), SSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+size_t elem_size(int dtype) { return dtype == SSD_BF16 ? 2 : 4; }
+
+bool check_cu(const int32_t* cu, int B, bool need_positive) {
+    if (cu[0] != 0) return false;
+    for (int b = 0; b < B; ++b) {
+        if (cu[b + 1] < cu[b]) return false;
+        if (need_positive && cu[b + 1] == cu[b]) return false;
+    }
+    return true;
+}
+
+// Stage `bytes` of host data and enqueue its upload to `dev`.
+int upload(ssd_ctx* c, const void* host, void* dev, size_t bytes) {
+    if (!bytes) return SSD_OK;
+    int slot; void* p;
+    HIP_TRY(c, c->stager.acquire(bytes, slot, p));
+    memcpy(p, host, bytes);
+    HIP_TRY(c, hipMemcpyAsync(dev, p, bytes, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, c->stager.commit(slot, c->stream));
+    return SSD_OK;
+}
+
+struct GatePlan { size_t H, arg, cu, total; };
+GatePlan plan_gate(int64_t frames, int64_t utts) {
+    GatePlan p;
+    size_t o = 0;
+    p.H = o; o = align_up(o + (size_t)frames * 4);
+    p.arg = o; o = align_up(o + (size_t)frames * 4);
+    p.cu = o; o = align_up(o + (size_t)(utts + 1) * 4);
+    p.total = o;
+    return p;
+}
+
+int attn_tile_rows(int dtype) { return dtype == SSD_BF16 ? 128 : 4; }
+
+struct VerifyPlan {
+    size_t row_src, pos, vrow, tiles, meta_bytes;     // metadata block, uploaded in one copy
+    size_t x, a, qkv, attn, gu, h, total;             // activations
+};
+VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t utts) {
+    VerifyPlan p;
+    const size_t es = elem_size(c.dtype);
+    const int64_t max_tiles = M / attn_tile_rows(c.dtype) + utts + 1;
+    size_t o = 0;
+    p.row_src = o; o = align_up(o + (size_t)M * 4);
+    p.pos = o; o = align_up(o + (size_t)M * 4);
+    p.vrow = o; o = align_up(o + (size_t)Mv * 4);
+    p.tiles = o; o = align_up(o + (size_t)max_tiles * sizeof(AttnTile));
+    p.meta_bytes = o;
+    const int64_t d = c.d_model, dq = (int64_t)c.n_q_heads * c.head_dim, dkv = (int64_t)c.n_kv_heads * c.head_dim;
+    p.x = o; o = align_up(o + (size_t)(M * d) * 4);
+    p.a = o; o = align_up(o + (size_t)(M * d) * es);
+    p.qkv = o; o = align_up(o + (size_t)(M * (dq + 2 * dkv)) * es);
+    p.attn = o; o = align_up(o + (size_t)(M * dq) * es);
+    p.gu = o; if (c.dtype == SSD_F32) o = align_up(o + (size_t)(M * 2 * c.d_ff) * 4);
+    p.h = o; o = align_up(o + (size_t)(M * c.d_ff) * es);
+    p.total = o;
+    return p;
+}
+
+struct AcceptPlan { size_t cu, part_ms, tgt, part_arg, total; };
+AcceptPlan plan_accept(const ssd_model_cfg& c, int64_t Mv, int64_t utts) {
+    AcceptPlan p;
+    size_t o = 0;
+    p.cu = o; o = align_up(o + (size_t)(utts + 1) * 4);
+    p.part_ms = p.tgt = p.part_arg = o;
+    if (c.dtype == SSD_BF16) {
+        const int64_t g = lmhead_col_groups(c.vocab);
+        p.part_ms = o; o = align_up(o + (size_t)(g * Mv) * sizeof(float2));
+        p.tgt = o; o = align_up(o + (size_t)Mv * 4);
+        p.part_arg = o; o = align_up(o + (size_t)(g * Mv) * sizeof(int2));
+    }
+    p.total = o;
+    return p;
+}
+
+int check_model(ssd_ctx* c, const ssd_model_cfg& m) {
+    if (m.n_layers <= 0 || m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.head_dim <= 0 ||
+        m.d_ff <= 0 || m.vocab <= 0 || m.max_positions <= 0 || !(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f))
+        return fail(c, SSD_EINVAL, "ssd_create: non-positive model dimension");
+    if (m.n_q_heads % m.n_kv_heads) return fail(c, SSD_ESHAPE, "ssd_create: n_q_heads must be a multiple of n_kv_heads");
+    const int dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
+    if (m.dtype == SSD_BF16) {
+        if (m.head_dim != 128) return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs head_dim 128 (got %d)", m.head_dim);
+        if (m.d_model % 128 || m.d_ff % 128 || dq % 128 || dkv % 128 || m.vocab % 128)
+            return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs d_model, d_ff, head widths and vocab to be multiples of 128");
+    } else if (m.dtype == SSD_F32) {
+        if (m.head_dim % 4 || m.head_dim > 128) return fail(c, SSD_ESHAPE, "ssd_create: f32 needs head_dim %% 4 == 0 and <= 128");
+        if (m.d_model % 16 || m.d_ff % 16 || dq % 16 || m.d_model > 1024)
+            return fail(c, SSD_ESHAPE, "ssd_create: f32 needs d_model, d_ff, n_q_heads*head_dim multiples of 16 and d_model <= 1024");
+    } else {
+        return fail(c, SSD_EUNSUPPORTED, "ssd_create: dtype %d", m.dtype);
+    }
+    return SSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ssd_last_error(const ssd_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, void* hip_stream) {
+    if (!out) return SSD_EINVAL;
+    *out = nullptr;
+    if ((cfg == nullptr) != (w == nullptr)) return SSD_EINVAL;
+    ssd_ctx* c = new ssd_ctx();
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    if (!cfg) { *out = c; return SSD_OK; }
+    int rc = check_model(c, *cfg);
+    if (rc == SSD_OK) {
+        const void* const* per_layer[] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->norm_attn, w->norm_mlp};
+        bool ok = w->embed && w->lm_head && w->norm_final;
+        for (auto arr : per_layer) {
+            ok = ok && arr;
+            for (int l = 0; ok && l < cfg->n_layers; ++l) ok = arr[l] != nullptr;
+        }
+        if (!ok) rc = fail(c, SSD_EINVAL, "ssd_create: NULL weight pointer");
+    }
+    if (rc != SSD_OK) { fprintf(stderr, "ssd_create: %s\n", c->err.c_str()); delete c; return rc; }
+    c->cfg = *cfg;
+    c->has_model = true;
+    c->embed = w->embed; c->lm_head = w->lm_head; c->norm_final = w->norm_final;
+    const int L = cfg->n_layers, d = cfg->d_model, dq = cfg->n_q_heads * cfg->head_dim, dkv = cfg->n_kv_heads * cfg->head_dim;
+    const int dff = cfg->d_ff;
+    const bool half = cfg->dtype == SSD_BF16;
+    const size_t es = elem_size(cfg->dtype);
+    auto bail = [&](hipError_t e, const char* what) {
+        fprintf(stderr, "ssd_create: %s: %s\n", what, hipGetErrorString(e));
+        ssd_destroy(c);
+        return (int)SSD_EHIP;
+    };
+    hipError_t e;
+    auto dev_alloc = [&](void** p, size_t bytes) {
+        hipError_t r = hipMalloc(p, bytes);
+        if (r == hipSuccess) c->owned.push_back(*p);
+        return r;
+    };
+    // largest magnitude of each weight group -> exact power-of-two scale into the f16 range
+    const int n_groups = 4 * L + 1;
+    std::vector<float> scale(n_groups, 1.0f);
+    if (half) {
+        unsigned int* d_max = nullptr;
+        if ((e = dev_alloc((void**)&d_max, (size_t)n_groups * 4)) != hipSuccess) return bail(e, "hipMalloc(absmax)");
+        if ((e = hipMemsetAsync(d_max, 0, (size_t)n_groups * 4, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync");
+        for (int l = 0; l < L; ++l) {
+            launch_absmax(cfg->dtype, w->wq[l], (int64_t)dq * d, d_max + 4 * l + 0, c->stream);
+            launch_absmax(cfg->dtype, w->wk[l], (int64_t)dkv * d, d_max + 4 * l + 0, c->stream);
+            launch_absmax(cfg->dtype, w->wv[l], (int64_t)dkv * d, d_max + 4 * l + 0, c->stream);
+            launch_absmax(cfg->dtype, w->wo[l], (int64_t)d * dq, d_max + 4 * l + 1, c->stream);
+            launch_absmax(cfg->dtype, w->w_gate[l], (int64_t)dff * d, d_max + 4 * l + 2, c->stream);
+            launch_absmax(cfg->dtype, w->w_up[l], (int64_t)dff * d, d_max + 4 * l + 2, c->stream);
+            launch_absmax(cfg->dtype, w->w_down[l], (int64_t)d * dff, d_max + 4 * l + 3, c->stream);
+        }
+        launch_absmax(cfg->dtype, w->lm_head, (int64_t)cfg->vocab * d, d_max + 4 * L, c->stream);
+        std::vector<float> mx(n_groups);
+        if ((e = hipMemcpyAsync(mx.data(), d_max, (size_t)n_groups * 4, hipMemcpyDeviceToHost, c->stream)) != hipSuccess)
+            return bail(e, "hipMemcpyAsync(absmax)");
+        if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "absmax");
+        for (int g = 0; g < n_groups; ++g) {
+            if (!(mx[g] > 0.f) || !std::isfinite(mx[g])) continue;
+            int ex;
+            frexpf(mx[g], &ex);                               // mx < 2^ex
+            scale[g] = ldexpf(1.0f, std::max(-60, std::min(60, 14 - ex)));   // largest value lands below 2^14
+        }
+    }
+    for (int l = 0; l < L; ++l) {
+        c->norm_attn.push_back(w->norm_attn[l]); c->norm_mlp.push_back(w->norm_mlp[l]);
+        void *pq = nullptr, *pg = nullptr;
+        if ((e = dev_alloc(&pq, (size_t)(dq + 2 * dkv) * d * es)) != hipSuccess) return bail(e, "hipMalloc(wqkv)");
+        c->wqkv.push_back(pq);
+        if ((e = dev_alloc(&pg, (size_t)2 * dff * d * es)) != hipSuccess) return bail(e, "hipMalloc(wgu)");
+        c->wgu.push_back(pg);
+        launch_pack_qkv(cfg->dtype, w->wq[l], w->wk[l], w->wv[l], pq, dq, dkv, d, cfg->head_dim, scale[4 * l + 0], c->stream);
+        launch_pack_gate_up(cfg->dtype, w->w_gate[l], w->w_up[l], pg, dff, d, scale[4 * l + 2], c->stream);
+        if (half) {
+            void *po = nullptr, *pd = nullptr;
+            if ((e = dev_alloc(&po, (size_t)d * dq * 2)) != hipSuccess) return bail(e, "hipMalloc(wo)");
+            if ((e = dev_alloc(&pd, (size_t)d * dff * 2)) != hipSuccess) return bail(e, "hipMalloc(w_down)");
+            launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, scale[4 * l + 1], c->stream);
+            launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, scale[4 * l + 3], c->stream);
+            c->wo.push_back(po); c->w_down.push_back(pd);
+        } else {
+            c->wo.push_back(w->wo[l]); c->w_down.push_back(w->w_down[l]);
+        }
+        c->ds_qkv.push_back(1.0f / scale[4 * l + 0]); c->ds_o.push_back(1.0f / scale[4 * l + 1]);
+        c->ds_gu.push_back(1.0f / scale[4 * l + 2]); c->ds_down.push_back(1.0f / scale[4 * l + 3]);
+    }
+    if (half) {
+        void* pl = nullptr;
+        if ((e = dev_alloc(&pl, (size_t)cfg->vocab * d * 2)) != hipSuccess) return bail(e, "hipMalloc(lm_head)");
+        launch_convert_weight(cfg->dtype, w->lm_head, pl, cfg->vocab, d, scale[4 * L], c->stream);
+        c->lm_head = pl;
+        c->ds_lm = 1.0f / scale[4 * L];
+    }
+    // rotary table, computed in double and rounded once
+    const int hd2 = cfg->head_dim / 2;
+    std::vector<float> tab((size_t)cfg->max_positions * hd2 * 2);
+    for (int p = 0; p < cfg->max_positions; ++p)
+        for (int i = 0; i < hd2; ++i) {
+            const double ang = (double)p * pow((double)cfg->rope_theta, -2.0 * i / cfg->head_dim);
+            tab[((size_t)p * hd2 + i) * 2] = (float)cos(ang);
+            tab[((size_t)p * hd2 + i) * 2 + 1] = (float)sin(ang);
+        }
+    if ((e = dev_alloc((void**)&c->rope_tab, tab.size() * 4)) != hipSuccess) return bail(e, "hipMalloc(rope)");
+    if ((e = hipMemcpyAsync(c->rope_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
+        return bail(e, "hipMemcpyAsync(rope)");
+    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "weight packing");
+    if ((e = hipGetLastError()) != hipSuccess) return bail(e, "weight packing launch");
+    *out = c;
+    return SSD_OK;
+}
+
+void ssd_destroy(ssd_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (void* p : c->owned) if (p) (void)hipFree(p);
+    c->stager.release();
+    delete c;
+}
+
+size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_tokens, int64_t max_verify_rows,
+                           int64_t max_utts) {
+    if (!ctx || max_frames < 0 || max_tokens < 0 || max_verify_rows < 0 || max_utts < 0) return 0;
+    size_t need = plan_gate(max_frames, max_utts).total;
+    if (ctx->has_model) {
+        need = std::max(need, plan_verify(ctx->cfg, max_tokens, max_verify_rows, max_utts).total);
+        need = std::max(need, plan_accept(ctx->cfg, max_verify_rows, max_utts).total);
+    }
+    return need + 256;
+}
+
+int ssd_set_workspace(ssd_ctx* ctx, void* dev_ptr, size_t bytes) {
+    if (!ctx) return SSD_EINVAL;
+    if (!dev_ptr && bytes) return fail(ctx, SSD_EINVAL, "workspace pointer is NULL");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return fail(ctx, SSD_EINVAL, "workspace must be 256-byte aligned");
+    ctx->ws = dev_ptr;
+    ctx->ws_bytes = bytes;
+    return SSD_OK;
+}
+
+int ctc_gate(ssd_ctx* ctx, const void* logits, int dtype, const int32_t* cu_frames, int B, int V_ctc, int blank_id,
+             float tau_ctc, float* frame_entropy, int32_t* frame_argmax, float* max_entropy, uint8_t* gate_pass,
+             int32_t* draft_ctc, int32_t* draft_len) {
+    if (!ctx) return SSD_EINVAL;
+    if (!logits || !cu_frames || !max_entropy || !gate_pass || !draft_ctc || !draft_len)
+        return fail(ctx, SSD_EINVAL, "ctc_gate: NULL argument");
+    if (B <= 0) return fail(ctx, SSD_EINVAL, "ctc_gate: B must be positive (got %d)", B);
+    if (V_ctc <= 0) return fail(ctx, SSD_EINVAL, "ctc_gate: V_ctc must be positive (got %d)", V_ctc);
+    if (blank_id < 0 || blank_id >= V_ctc) return fail(ctx, SSD_EINVAL, "ctc_gate: blank_id %d outside [0, %d)", blank_id, V_ctc);
+    if (dtype != SSD_F32 && dtype != SSD_BF16) return fail(ctx, SSD_EUNSUPPORTED, "ctc_gate: dtype %d", dtype);
+    if (!check_cu(cu_frames, B, true))
+        return fail(ctx, SSD_EINVAL, "ctc_gate: cu_frames must start at 0 and increase strictly (every utterance needs a frame)");
+    const int64_t n_rows = cu_frames[B];
+    const GatePlan p = plan_gate(n_rows, B);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "ctc_gate: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+    char* ws = static_cast<char*>(ctx->ws);
+    float* H = frame_entropy ? frame_entropy : reinterpret_cast<float*>(ws + p.H);
+    int32_t* arg = frame_argmax ? frame_argmax : reinterpret_cast<int32_t*>(ws + p.arg);
+    int32_t* cu_dev = reinterpret_cast<int32_t*>(ws + p.cu);
+    int rc = upload(ctx, cu_frames, cu_dev, (size_t)(B + 1) * 4);
+    if (rc != SSD_OK) return rc;
+    launch_gate(logits, dtype, n_rows, V_ctc, cu_dev, B, blank_id, tau_ctc, H, arg, max_entropy, gate_pass, draft_ctc,
+                draft_len, ctx->stream);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, const int32_t* prompt_ids,
+                   const int32_t* cu_prompt, const int32_t* draft_ids, const int32_t* cu_draft, int Bv, void* h_verify) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->has_model) return fail(ctx, SSD_EINVAL, "verify_forward: context was created without a model");
+    if (!cu_speech || !cu_prompt || !cu_draft) return fail(ctx, SSD_EINVAL, "verify_forward: NULL cu_* array");
+    if (Bv <= 0) return fail(ctx, SSD_EINVAL, "verify_forward: Bv must be positive (got %d)", Bv);
+    if (!check_cu(cu_speech, Bv, false) || !check_cu(cu_prompt, Bv, false) || !check_cu(cu_draft, Bv, false))
+        return fail(ctx, SSD_EINVAL, "verify_forward: cu_* arrays must start at 0 and be non-decreasing");
+    const ssd_model_cfg& m = ctx->cfg;
+    const int64_t sum_S = cu_speech[Bv], sum_P = cu_prompt[Bv], Mv = cu_draft[Bv];
+    const int64_t M = sum_S + sum_P + Mv;
+    if ((sum_S && !speech_emb) || (sum_P && !prompt_ids) || (Mv && (!draft_ids || !h_verify)))
+        return fail(ctx, SSD_EINVAL, "verify_forward: NULL data pointer");
+    if (M > 0x3fffffff) return fail(ctx, SSD_ESHAPE, "verify_forward: too many rows");
+    const int tile_rows = attn_tile_rows(m.dtype);
+    for (int b = 0; b < Bv; ++b) {
+        const int S = cu_speech[b + 1] - cu_speech[b], P = cu_prompt[b + 1] - cu_prompt[b], U = cu_draft[b + 1] - cu_draft[b];
+        if (S + P < 1) return fail(ctx, SSD_EINVAL, "verify_forward: utterance %d has no speech or prompt row", b);
+        if (S + P + U > m.max_positions)
+            return fail(ctx, SSD_ESHAPE, "verify_forward: utterance %d has %d rows, max_positions is %d", b, S + P + U, m.max_positions);
+    }
+    const VerifyPlan p = plan_verify(m, M, Mv, Bv);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "verify_forward: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+
+    // ---- host metadata: source of every decoder row, its position, verification rows, attention tiles
+    std::vector<char> meta(p.meta_bytes);
+    int32_t* row_src = reinterpret_cast<int32_t*>(meta.data() + p.row_src);
+    int32_t* pos = reinterpret_cast<int32_t*>(meta.data() + p.pos);
+    int32_t* vrow = reinterpret_cast<int32_t*>(meta.data() + p.vrow);
+    AttnTile* tiles = reinterpret_cast<AttnTile*>(meta.data() + p.tiles);
+    int n_tiles = 0;
+    int64_t r = 0;
+    for (int b = 0; b < Bv; ++b) {
+        const int S = cu_speech[b + 1] - cu_speech[b], P = cu_prompt[b + 1] - cu_prompt[b], U = cu_draft[b + 1] - cu_draft[b];
+        const int n = S + P + U;
+        const int start = (int)r;
+        for (int i = 0; i < S; ++i, ++r) { row_src[r] = cu_speech[b] + i; pos[r] = i; }
+        for (int i = 0; i < P; ++i, ++r) { row_src[r] = SRC_PROMPT | (cu_prompt[b] + i); pos[r] = S + i; }
+        for (int i = 0; i < U; ++i, ++r) { row_src[r] = SRC_DRAFT | (cu_draft[b] + i); pos[r] = S + P + i; }
+        // draft token i (1-based) is scored by sequence index S + P + i - 2
+        for (int i = 1; i <= U; ++i) vrow[cu_draft[b] + i - 1] = start + S + P + i - 2;
+        for (int q = 0; q < n; q += tile_rows) tiles[n_tiles++] = AttnTile{start, n, q, 0};
+    }
+    char* ws = static_cast<char*>(ctx->ws);
+    int rc = upload(ctx, meta.data(), ws, p.meta_bytes);
+    if (rc != SSD_OK) return rc;
+    const int32_t* d_row_src = reinterpret_cast<const int32_t*>(ws + p.row_src);
+    const int32_t* d_pos = reinterpret_cast<const int32_t*>(ws + p.pos);
+    const int32_t* d_vrow = reinterpret_cast<const int32_t*>(ws + p.vrow);
+    const AttnTile* d_tiles = reinterpret_cast<const AttnTile*>(ws + p.tiles);
+    float* x = reinterpret_cast<float*>(ws + p.x);
+    void* a = ws + p.a;
+    void* qkv = ws + p.qkv;
+    void* att = ws + p.attn;
+    void* h = ws + p.h;
+    hipStream_t st = ctx->stream;
+    const int Mi = (int)M, d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
+
+    launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, st);
+    for (int l = 0; l < m.n_layers; ++l) {
+        launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, st);
+        if (m.dtype == SSD_BF16) {
+            launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st);
+            launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st);
+            launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, Mi, d, dq, ctx->ds_o[l], st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st);
+            launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Mi, m.d_ff, d, ctx->ds_gu[l], st);
+            launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, Mi, d, m.d_ff, ctx->ds_down[l], st);
+        } else {
+            float* gu = reinterpret_cast<float*>(ws + p.gu);
+            launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
+            launch_rope_f32((float*)qkv, d_pos, ctx->rope_tab, Mi, m.n_q_heads + m.n_kv_heads, m.head_dim, dq + 2 * dkv, st);
+            launch_attn_f32((const float*)qkv, (float*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, m.head_dim, st);
+            launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Mi, d, dq, F32_ADD, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st);
+            launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Mi, 2 * m.d_ff, d, F32_STORE, st);
+            launch_swiglu_f32(gu, (float*)h, Mi, m.d_ff, st);
+            launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Mi, d, m.d_ff, F32_ADD, st);
+        }
+    }
+    // verification rows only: final RMSNorm of the positions that score a draft token
+    launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, st);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int accept_prefix(ssd_ctx* ctx, const void* h_verify, const int32_t* draft_ids, const int32_t* cu_draft, int Bv,
+                  float tau_slm, float* draft_logp, int32_t* accept_len, uint8_t* all_accepted, int32_t* greedy_tok) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->has_model) return fail(ctx, SSD_EINVAL, "accept_prefix: context was created without a model");
+    if (!cu_draft || !accept_len || !all_accepted) return fail(ctx, SSD_EINVAL, "accept_prefix: NULL argument");
+    if (Bv <= 0) return fail(ctx, SSD_EINVAL, "accept_prefix: Bv must be positive (got %d)", Bv);
+    if (!check_cu(cu_draft, Bv, false)) return fail(ctx, SSD_EINVAL, "accept_prefix: cu_draft must start at 0 and be non-decreasing");
+    if (tau_slm != tau_slm) return fail(ctx, SSD_EINVAL, "accept_prefix: tau_slm is NaN");
+    const int64_t Mv = cu_draft[Bv];
+    if (Mv && (!h_verify || !draft_ids || !draft_logp)) return fail(ctx, SSD_EINVAL, "accept_prefix: NULL data pointer");
+    const ssd_model_cfg& m = ctx->cfg;
+    const AcceptPlan p = plan_accept(m, Mv, Bv);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "accept_prefix: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+    char* ws = static_cast<char*>(ctx->ws);
+    int32_t* cu_dev = reinterpret_cast<int32_t*>(ws + p.cu);
+    int rc = upload(ctx, cu_draft, cu_dev, (size_t)(Bv + 1) * 4);
+    if (rc != SSD_OK) return rc;
+    hipStream_t st = ctx->stream;
+    if (m.dtype == SSD_BF16) {
+        float2* part_ms = reinterpret_cast<float2*>(ws + p.part_ms);
+        float* tgt = reinterpret_cast<float*>(ws + p.tgt);
+        int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
+        launch_lmhead_mfma((const uint16_t*)h_verify, (const uint16_t*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,
+                           part_ms, tgt, part_arg, greedy_tok != nullptr, ctx->ds_lm, st);
+        launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), (int)Mv, draft_logp, greedy_tok, st);
+    } else {
+        launch_lmhead_f32((const float*)h_verify, (const float*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,
+                          draft_logp, greedy_tok, st);
+    }
+    // ln(tau) in double, rounded once to fp32; tau <= 0 accepts every token
+    const float ln_tau = tau_slm > 0.f ? (float)log((double)tau_slm) : -INFINITY;
+    launch_accept_scan(draft_logp, cu_dev, Bv, ln_tau, accept_len, all_accepted, st);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,170 @@
+// Causal self-attention over ragged (varlen) utterances, head_dim 128, grouped KV heads, f16 MFMA.
+// This is the mechanism that lets Eq. 5 be evaluated for all draft tokens in one forward (Sec. 2.2):
+// position p only attends to positions <= p of its own utterance.
+//
+// A workgroup of 4 wavefronts owns 128 query positions of one (utterance, query head); each
+// wavefront owns 32 of them.  Keys/values are visited in blocks of 64 with an online softmax.
+//   S^T[key, q]  = K . Q^T      (A operand: K rows from LDS, B operand: Q rows held in registers)
+//   O^T[dim, q] += V^T . P^T    (A operand: V^T rows from LDS, B operand: P^T)
+// Working with the transposed products keeps a query position in one lane column (lane%32) for
+// both MFMAs, so the softmax statistics are per-lane scalars and the fp32 accumulator registers of
+// S^T turn into the B operand of the second MFMA after an f16 pack, without any data exchange.
+// The k-slot order of that operand is the accumulator's row order, so V^T is written to LDS with
+// the keys of every group of 16 permuted the same way (bits 2 and 3 of the key index swapped).
+#include "gemm_core.h"
+#include "ssd_internal.h"
+
+namespace ssd {
+
+constexpr int ATT_HD = 128;
+constexpr int ATT_KB = 64;                    // keys per block
+constexpr int ATT_K_STRIDE = ATT_HD + 8;      // Ks[key][dim], elements
+constexpr int ATT_V_STRIDE = ATT_KB + 8;      // Vt[dim][slot], elements
+
+__global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
+                                                        const AttnTile* __restrict__ tiles, int n_q_heads,
+                                                        int n_kv_heads) {
+    __shared__ __align__(16) f16_t Ks[ATT_KB * ATT_K_STRIDE];
+    __shared__ __align__(16) f16_t Vt[ATT_HD * ATT_V_STRIDE];
+    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int hgrp = lane / 32, lcol = lane % 32;
+    const AttnTile t = tiles[blockIdx.x];
+    const int head = blockIdx.y;
+    const int kvh = head / (n_q_heads / n_kv_heads);
+    const int d_q = n_q_heads * ATT_HD, d_kv = n_kv_heads * ATT_HD;
+    const int ldq = d_q + 2 * d_kv;
+    const f16_t* seq = qkv + (int64_t)t.seq_start * ldq;
+    const f16_t* kbase = seq + d_q + kvh * ATT_HD;
+    const f16_t* vbase = kbase + d_kv;
+
+    const int q_first = t.q_start + wave * 32;          // first query position of this wavefront
+    const int qpos = q_first + lcol;
+    const bool wave_live = q_first < t.seq_len;
+
+    // Q^T fragments: lane supplies query row qpos, dims 16*kk + 8*hgrp .. +8
+    f16x8_t qf[8];
+    {
+        const int qrow = min(qpos, t.seq_len - 1);
+        const uint4* src = reinterpret_cast<const uint4*>(seq + (int64_t)qrow * ldq + head * ATT_HD + hgrp * 8);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) qf[kk] = as_f16x8(src[kk * 2]);
+    }
+    f32x16_t o_acc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sc = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(128)
+
+    const int kv_end = min(t.seq_len, t.q_start + 128);             // keys needed by this tile
+    for (int kb = 0; kb < kv_end; kb += ATT_KB) {
+        // ---- stage K (row-major) and V (transposed, permuted) blocks
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = tid + it * 256;
+            const int key = c / 16, dc = c % 16;
+            const int krow = min(kb + key, t.seq_len - 1);
+            const uint4 kv = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + dc * 8);
+            *reinterpret_cast<uint4*>(Ks + key * ATT_K_STRIDE + dc * 8) = kv;
+            const uint4 vv = *reinterpret_cast<const uint4*>(vbase + (int64_t)krow * ldq + dc * 8);
+            const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
+            f16_t* vd = Vt + (dc * 8) * ATT_V_STRIDE + slot;
+            vd[0 * ATT_V_STRIDE] = (f16_t)(vv.x & 0xffff); vd[1 * ATT_V_STRIDE] = (f16_t)(vv.x >> 16);
+            vd[2 * ATT_V_STRIDE] = (f16_t)(vv.y & 0xffff); vd[3 * ATT_V_STRIDE] = (f16_t)(vv.y >> 16);
+            vd[4 * ATT_V_STRIDE] = (f16_t)(vv.z & 0xffff); vd[5 * ATT_V_STRIDE] = (f16_t)(vv.z >> 16);
+            vd[6 * ATT_V_STRIDE] = (f16_t)(vv.w & 0xffff); vd[7 * ATT_V_STRIDE] = (f16_t)(vv.w >> 16);
+        }
+        __syncthreads();
+        if (wave_live && kb <= q_first + 31) {
+            // ---- S^T for the two 32-key halves of the block
+            f32x16_t s_acc[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_acc[c][r] = 0.f;
+                const f16_t* kf = Ks + (c * 32 + lcol) * ATT_K_STRIDE + hgrp * 8;
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk)
+                    s_acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        as_f16x8(*reinterpret_cast<const uint4*>(kf + kk * 16)), qf[kk], s_acc[c], 0, 0, 0);
+            }
+            // ---- causal mask (only blocks that reach past the first query of the wavefront)
+            if (kb + ATT_KB - 1 > q_first) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int kpos = kb + c * 32 + 8 * (r / 4) + 4 * hgrp + (r % 4);
+                        if (kpos > qpos) s_acc[c][r] = -INFINITY;
+                    }
+            }
+            // ---- online softmax; lanes l and l^32 share a query position
+            float bm = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) bm = fmaxf(bm, s_acc[c][r]);
+            bm = fmaxf(bm, __shfl_xor(bm, 32));
+            const float m_new = fmaxf(m_run, bm);
+            const float alpha = exp2f((m_run - m_new) * sc);
+            const float ms = m_new * sc;
+            float rs = 0.f;
+            f16x8_t pf[4];
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p0 = exp2f(fmaf(s_acc[c][8 * s + 2 * e], sc, -ms));
+                        const float p1 = exp2f(fmaf(s_acc[c][8 * s + 2 * e + 1], sc, -ms));
+                        rs += p0 + p1;
+                        w[e] = pack_f16x2(p0, p1);
+                    }
+                    pf[c * 2 + s] = as_f16x8(make_uint4(w[0], w[1], w[2], w[3]));
+                }
+            rs += __shfl_xor(rs, 32);
+            l_run = l_run * alpha + rs;
+            m_run = m_new;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+            // ---- O^T += V^T . P^T
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const f16_t* vf = Vt + (db * 32 + lcol) * ATT_V_STRIDE + hgrp * 8;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        as_f16x8(*reinterpret_cast<const uint4*>(vf + ks * 16)), pf[ks], o_acc[db], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+    if (qpos < t.seq_len) {
+        const float inv = 1.0f / l_run;
+        f16_t* o = out + (int64_t)(t.seq_start + qpos) * d_q + head * ATT_HD;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int dim = db * 32 + 8 * g + 4 * hgrp;
+                uint2 w;
+                w.x = pack_f16x2(o_acc[db][4 * g] * inv, o_acc[db][4 * g + 1] * inv);
+                w.y = pack_f16x2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
+                *reinterpret_cast<uint2*>(o + dim) = w;
+            }
+    }
+}
+
+void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
+                      int n_kv_heads, hipStream_t st) {
+    if (n_tiles <= 0) return;
+    hipLaunchKernelGGL(attn_mfma_kernel, dim3(n_tiles, n_q_heads), dim3(256), 0, st, qkv, out, tiles, n_q_heads,
+                       n_kv_heads);
+}
+
+}  // namespace ssd

@@ -1,0 +1,77 @@
+// Small device helpers shared by the kernels: bf16 <-> fp32 bit moves, lane-group reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssd {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (finite inputs; NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// fp32 -> IEEE half bits, round to nearest even (v_cvt_f16_f32)
+typedef uint16_t f16_t;    // raw IEEE binary16 bits
+__device__ __forceinline__ f16_t f32_to_f16(float f) { return __builtin_bit_cast(f16_t, (_Float16)f); }
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    return (uint32_t)f32_to_f16(lo) | ((uint32_t)f32_to_f16(hi) << 16);
+}
+__device__ __forceinline__ float f16_to_f32(f16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
+
+// Data-parallel-primitive lane moves inside a row of 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <-> 7-i inside each 8
+constexpr int DPP_MIRROR = 0x140;       // lane i <-> 15-i inside each 16
+
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+struct OpSum { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMinI { __device__ __forceinline__ int operator()(int a, int b) const { return a < b ? a : b; } };
+
+// All-reduce over groups of W consecutive lanes (W = 16 or 64); every lane gets the result.
+template <int W, class Op>
+__device__ __forceinline__ float group_allreduce(float v, Op op) {
+    v = op(v, dpp_f<DPP_XOR1>(v));
+    v = op(v, dpp_f<DPP_XOR2>(v));
+    v = op(v, dpp_f<DPP_HALF_MIRROR>(v));
+    v = op(v, dpp_f<DPP_MIRROR>(v));
+    if (W > 16) {
+        v = op(v, __shfl_xor(v, 16));
+        v = op(v, __shfl_xor(v, 32));
+    }
+    return v;
+}
+template <int W, class Op>
+__device__ __forceinline__ int group_allreduce_i(int v, Op op) {
+    v = op(v, dpp_i<DPP_XOR1>(v));
+    v = op(v, dpp_i<DPP_XOR2>(v));
+    v = op(v, dpp_i<DPP_HALF_MIRROR>(v));
+    v = op(v, dpp_i<DPP_MIRROR>(v));
+    if (W > 16) {
+        v = op(v, __shfl_xor(v, 16));
+        v = op(v, __shfl_xor(v, 32));
+    }
+    return v;
+}
+
+}  // namespace ssd

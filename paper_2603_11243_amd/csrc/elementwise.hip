@@ -1,0 +1,231 @@
+// Memory-bound helpers of the decoder forward: input-row assembly, RMSNorm, weight re-layout,
+// and the first-failing-token scan of the acceptance rule.
+#include <algorithm>
+
+#include "device_utils.h"
+#include "ssd_internal.h"
+
+namespace ssd {
+
+// ---------------------------------------------------------------------------------------------
+// Input assembly (Sec. 2.2: the LLM sees the speech embeddings g, the prompt and the draft prefix):
+// decoder row r <- speech_emb[src] or embed[token id], widened to the fp32 residual stream.
+template <typename T>
+__global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ speech_emb, const T* __restrict__ embed,
+                                                         const int32_t* __restrict__ prompt_ids,
+                                                         const int32_t* __restrict__ draft_ids,
+                                                         const int32_t* __restrict__ row_src, int M, int d, int vocab,
+                                                         float* __restrict__ x) {
+    const int r = blockIdx.x;
+    const int32_t code = row_src[r];
+    const T* src;
+    if (code & SRC_DRAFT) {
+        int id = draft_ids[code & SRC_MASK];
+        id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+        src = embed + (int64_t)id * d;
+    } else if (code & SRC_PROMPT) {
+        int id = prompt_ids[code & SRC_MASK];
+        id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+        src = embed + (int64_t)id * d;
+    } else {
+        src = speech_emb + (int64_t)code * d;
+    }
+    float* dst = x + (int64_t)r * d;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        if constexpr (sizeof(T) == 2) dst[i] = bf16_to_f32(src[i]); else dst[i] = src[i];
+    }
+}
+
+void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
+                       const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
+                       hipStream_t st) {
+    if (M <= 0) return;
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t*)speech_emb,
+                           (const bf16_t*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x);
+    else
+        hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)speech_emb,
+                           (const float*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x);
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: out[r] = x[row] * gain / sqrt(mean(x[row]^2) + eps), row = row_idx ? row_idx[r] : r.
+// One wavefront per row; statistics in fp32.  d must be a multiple of 4.
+// T = bf16 gain with f16 output (MFMA operand type), or fp32 gain with fp32 output.
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+                                                      const int32_t* __restrict__ row_idx, int n_rows, int d,
+                                                      float eps, T* __restrict__ out) {
+    const int lane = threadIdx.x % 64;
+    const int r = blockIdx.x * 4 + threadIdx.x / 64;
+    if (r >= n_rows) return;
+    const int64_t row = row_idx ? row_idx[r] : r;
+    const float4* src = reinterpret_cast<const float4*>(x + row * d);
+    const int n4 = d / 4;
+    float ss = 0.f;
+    for (int i = lane; i < n4; i += 64) {
+        const float4 v = src[i];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = group_allreduce<64>(ss, OpSum());
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    T* dst = out + (int64_t)r * d;
+    for (int i = lane; i < n4; i += 64) {
+        const float4 v = src[i];
+        if constexpr (sizeof(T) == 2) {
+            const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
+            uint2 o;
+            o.x = pack_f16x2(v.x * inv * bf16_lo(g.x), v.y * inv * bf16_hi(g.x));
+            o.y = pack_f16x2(v.z * inv * bf16_lo(g.y), v.w * inv * bf16_hi(g.y));
+            reinterpret_cast<uint2*>(dst)[i] = o;
+        } else {
+            const float4 g = reinterpret_cast<const float4*>(gain)[i];
+            reinterpret_cast<float4*>(dst)[i] = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+        }
+    }
+}
+
+void launch_rmsnorm(int dtype, const float* x, const void* gain, const int32_t* row_idx, int n_rows, int d, float eps,
+                    void* out, hipStream_t st) {
+    if (n_rows <= 0) return;
+    const unsigned grid = (unsigned)((n_rows + 3) / 4);
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, n_rows, d, eps, (bf16_t*)out);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(grid), dim3(256), 0, st, x, (const float*)gain, row_idx, n_rows, d, eps, (float*)out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight re-layout (once, at context creation).
+//
+// bf16 weights become f16 MFMA operands: w * scale with scale a power of two chosen from the
+// tensor's largest magnitude, so every bf16 value (8 significant bits) is represented exactly.
+// fp32 weights are copied unchanged (scale 1).
+template <typename T> struct Packed;
+template <> struct Packed<float> { typedef float type; static __device__ __forceinline__ float cvt(float v, float) { return v; } };
+template <> struct Packed<bf16_t> { typedef f16_t type; static __device__ __forceinline__ f16_t cvt(bf16_t v, float scale) { return f32_to_f16(bf16_to_f32(v) * scale); } };
+
+template <typename T>
+__global__ void absmax_kernel(const T* __restrict__ w, int64_t n, unsigned int* __restrict__ out) {
+    float m = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        float v;
+        if constexpr (sizeof(T) == 2) v = bf16_to_f32(w[i]); else v = w[i];
+        m = fmaxf(m, fabsf(v));
+    }
+    m = group_allreduce<64>(m, OpMax());
+    if (threadIdx.x % 64 == 0) atomicMax(out, __float_as_uint(m));      // non-negative floats order like their bits
+}
+
+void launch_absmax(int dtype, const void* w, int64_t n, unsigned int* out, hipStream_t st) {
+    const unsigned grid = (unsigned)std::min<int64_t>((n + 255) / 256, 2048);
+    if (dtype == SSD_BF16) hipLaunchKernelGGL(absmax_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)w, n, out);
+    else hipLaunchKernelGGL(absmax_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)w, n, out);
+}
+
+template <typename T>
+__global__ void convert_rows_kernel(const T* __restrict__ w, typename Packed<T>::type* __restrict__ out, int cols, float scale) {
+    const T* src = w + (int64_t)blockIdx.x * cols;
+    typename Packed<T>::type* dst = out + (int64_t)blockIdx.x * cols;
+    for (int i = threadIdx.x; i < cols; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+}
+
+void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, hipStream_t st) {
+    if (dtype == SSD_BF16) hipLaunchKernelGGL(convert_rows_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)w, (f16_t*)out, cols, scale);
+    else hipLaunchKernelGGL(convert_rows_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)w, (float*)out, cols, scale);
+}
+//
+// Fused QKV: rows [q heads | k heads | v heads].  Inside every rotary head (q and k) rows are
+// regrouped into blocks of 64 = [32 rows of the first half | their 32 rotation partners], so that
+// the GEMM epilogue finds a column and its partner (i, i + head_dim/2) in the same lane of two
+// neighbouring 32-wide accumulator blocks.  The f32 path keeps the natural order.
+template <typename T>
+__global__ void pack_qkv_kernel(const T* __restrict__ wq, const T* __restrict__ wk, const T* __restrict__ wv,
+                                typename Packed<T>::type* __restrict__ out, int d_q, int d_kv, int d_model, int head_dim,
+                                int permute, float scale) {
+    const int p = blockIdx.x;                       // packed row
+    int orig = p;
+    const int d_rot = d_q + d_kv;
+    if (permute && p < d_rot) {
+        const int half = head_dim / 2;
+        const int head = p / head_dim, w = p % head_dim;
+        const int grp = w / 64, in = w % 64;       // group of 64 packed rows inside the head
+        const int blk = in / 32, o = in % 32;
+        orig = head * head_dim + blk * half + grp * 32 + o;
+    }
+    const T* src = orig < d_q ? wq + (int64_t)orig * d_model
+                 : orig < d_q + d_kv ? wk + (int64_t)(orig - d_q) * d_model
+                 : wv + (int64_t)(orig - d_q - d_kv) * d_model;
+    typename Packed<T>::type* dst = out + (int64_t)p * d_model;
+    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+}
+
+void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, void* out, int d_q, int d_kv,
+                     int d_model, int head_dim, float scale, hipStream_t st) {
+    const int rows = d_q + 2 * d_kv;
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(pack_qkv_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)wq, (const bf16_t*)wk,
+                           (const bf16_t*)wv, (f16_t*)out, d_q, d_kv, d_model, head_dim, 1, scale);
+    else
+        hipLaunchKernelGGL(pack_qkv_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)wq, (const float*)wk,
+                           (const float*)wv, (float*)out, d_q, d_kv, d_model, head_dim, 0, 1.0f);
+}
+
+// Fused gate/up: bf16 packs blocks of 64 rows = [32 gate rows | the same 32 up rows]; f32 packs
+// [all gate rows | all up rows].
+template <typename T>
+__global__ void pack_gate_up_kernel(const T* __restrict__ wg, const T* __restrict__ wu,
+                                    typename Packed<T>::type* __restrict__ out, int d_ff, int d_model, int interleave,
+                                    float scale) {
+    const int p = blockIdx.x;
+    const T* src;
+    if (interleave) {
+        const int grp = p / 64, in = p % 64;
+        const int f = grp * 32 + in % 32;
+        src = (in < 32 ? wg : wu) + (int64_t)f * d_model;
+    } else {
+        src = p < d_ff ? wg + (int64_t)p * d_model : wu + (int64_t)(p - d_ff) * d_model;
+    }
+    typename Packed<T>::type* dst = out + (int64_t)p * d_model;
+    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+}
+
+void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
+                         hipStream_t st) {
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(pack_gate_up_kernel<bf16_t>, dim3(2 * d_ff), dim3(256), 0, st, (const bf16_t*)wg,
+                           (const bf16_t*)wu, (f16_t*)out, d_ff, d_model, 1, scale);
+    else
+        hipLaunchKernelGGL(pack_gate_up_kernel<float>, dim3(2 * d_ff), dim3(256), 0, st, (const float*)wg,
+                           (const float*)wu, (float*)out, d_ff, d_model, 0, 1.0f);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Acceptance (Eq. 5 and the definition of j in Sec. 2.3): token i passes iff logp_i > ln(tau);
+// accept_len = (index of the first failing token) - 1, or U when none fails.
+// One wavefront per utterance.
+__global__ void __launch_bounds__(64) accept_scan_kernel(const float* __restrict__ logp,
+                                                         const int32_t* __restrict__ cu_draft, float ln_tau,
+                                                         int32_t* __restrict__ accept_len,
+                                                         uint8_t* __restrict__ all_accepted) {
+    const int b = blockIdx.x;
+    const int lo = cu_draft[b], hi = cu_draft[b + 1];
+    const int U = hi - lo;
+    int first_fail = U;                                  // 0-based index of the first failing token
+    for (int i = threadIdx.x; i < U; i += 64) {
+        if (!(logp[lo + i] > ln_tau)) { first_fail = i; break; }
+    }
+    first_fail = group_allreduce_i<64>(first_fail, OpMinI());
+    if (threadIdx.x == 0) {
+        accept_len[b] = first_fail;
+        all_accepted[b] = first_fail == U ? 1 : 0;
+    }
+}
+
+void launch_accept_scan(const float* logp, const int32_t* cu_draft_dev, int Bv, float ln_tau, int32_t* accept_len,
+                        uint8_t* all_accepted, hipStream_t st) {
+    if (Bv <= 0) return;
+    hipLaunchKernelGGL(accept_scan_kernel, dim3(Bv), dim3(64), 0, st, logp, cu_draft_dev, ln_tau, accept_len, all_accepted);
+}
+
+}  // namespace ssd

@@ -1,0 +1,157 @@
+// The three projection GEMMs of a decoder layer (Eq. 4's network), f16 MFMA with fused epilogues:
+//   QKV      : a[M,d] x Wqkv^T  -> rotary embedding on q,k in fp32 -> f16 qkv[M, d_q + 2 d_kv]
+//   residual : o[M,K] x W^T     -> x[M,N] += acc                (attention output and MLP down projection)
+//   SwiGLU   : b[M,d] x Wgu^T   -> h[M,d_ff] = silu(gate) * up  (f16)
+// Every epilogue first multiplies the accumulator by `descale`, the inverse of the power of two the
+// weight tensor was scaled by when it was converted to f16.
+// The fused weight layouts are produced by pack_qkv_kernel / pack_gate_up_kernel: a column and the
+// column it must be combined with sit in neighbouring 32-wide accumulator blocks of the same lane.
+#include "gemm_core.h"
+#include "ssd_internal.h"
+
+namespace ssd {
+
+// Workgroup id -> tile.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each
+// with its own L2; ids are first regrouped so that one XCD walks a contiguous run of tiles, and
+// tiles are ordered in bands of GROUP_M row-tiles so that the run reuses few A and W panels.
+__device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_m, int tiles_n, int& tm, int& tn) {
+    constexpr int XCDS = 8, GROUP_M = 4;
+    const int per = total / XCDS, rem = total % XCDS;
+    const int xcd = pid % XCDS, idx = pid / XCDS;
+    const int v = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    const int band = v / (GROUP_M * tiles_n);
+    const int first_m = band * GROUP_M;
+    const int rows = min(tiles_m - first_m, GROUP_M);
+    const int in = v % (GROUP_M * tiles_n);
+    tm = first_m + in % rows;
+    tn = in / rows;
+}
+
+struct EpiResidual {
+    float* x; int ldx; float descale;
+    template <int TM, int TN>
+    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + acc_row(i, r, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float* p = x + (int64_t)row * ldx + col0 + acc_col(j, lane);
+                    *p += acc[i][j][r] * descale;
+                }
+            }
+    }
+};
+
+struct EpiQkvRope {
+    f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
+    const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
+    template <int TM, int TN>
+    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        static_assert(TN % 2 == 0, "rotation partners live in block pairs");
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+            const int p = col0 + j * 32;                    // packed column of this block pair (multiple of 64)
+            const bool rot = p < d_rot;
+            const int head = p / 128, grp = (p % 128) / 64;
+            const int i_rot = grp * 32 + lane % 32;
+            const int c0 = rot ? head * 128 + i_rot : p + lane % 32;
+            const int c1 = rot ? c0 + 64 : c0 + 32;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = row0 + acc_row(i, r, lane);
+                    if (row >= M) continue;
+                    float a = acc[i][j][r] * descale, b = acc[i][j + 1][r] * descale;
+                    if (rot) {
+                        const float2 cs = rope_tab[(int64_t)pos[row] * 64 + i_rot];
+                        const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
+                        a = ra; b = rb;
+                    }
+                    f16_t* o = qkv + (int64_t)row * ldq;
+                    o[c0] = f32_to_f16(a);
+                    o[c1] = f32_to_f16(b);
+                }
+        }
+    }
+};
+
+struct EpiSwiglu {
+    f16_t* h; int d_ff; float descale;
+    template <int TM, int TN>
+    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        static_assert(TN % 2 == 0, "gate/up live in block pairs");
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+            const int f = (col0 + j * 32) / 2 + lane % 32;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = row0 + acc_row(i, r, lane);
+                    if (row >= M) continue;
+                    const float g = acc[i][j][r] * descale, u = acc[i][j + 1][r] * descale;
+                    h[(int64_t)row * d_ff + f] = f32_to_f16(g / (1.0f + __expf(-g)) * u);
+                }
+        }
+    }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
+gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
+    using Tile = GemmTile<BM, BN, WAVES_M, WAVES_N>;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    f32x16_t acc[Tile::TM][Tile::TN];
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    Tile::run(A, W, M, K, tm * BM, tn * BN, reinterpret_cast<f16_t*>(smem_raw), acc);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= 0) return;
+    auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, Epi>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    static bool attr_set = false;
+    if (!attr_set && lds > 48 * 1024) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    const int tiles = ((M + BM - 1) / BM) * (N / BN);
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, epi);
+}
+
+void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
+                          const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale, hipStream_t st) {
+    const int N = d_q + 2 * d_kv;
+    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab)};
+    launch_gemm<128, 128, 2, 2>(A, Wqkv_packed, M, N, d_model, epi, st);
+}
+
+void launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, int M, int N, int K, float descale, hipStream_t st) {
+    EpiResidual epi{x, N, descale};
+    launch_gemm<128, 128, 2, 2>(A, W, M, N, K, epi, st);
+}
+
+void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
+                        float descale, hipStream_t st) {
+    EpiSwiglu epi{h, d_ff, descale};
+    launch_gemm<128, 128, 2, 2>(A, Wgu_packed, M, 2 * d_ff, K, epi, st);
+}
+
+}  // namespace ssd

@@ -1,0 +1,150 @@
+// Fused LM head + vocabulary log-softmax + draft-token gather (the likelihoods of Eq. 5, Sec. 2.2).
+//
+// logits[r, v] = h_verify[r] . W_lm[v] are produced tile by tile in MFMA accumulators and reduced on
+// the spot: every wavefront turns its [rows x WTN columns] slab into a partial (max, sum exp) per
+// row, the lane that holds column draft_ids[r] writes that logit, and (optionally) a partial argmax
+// is kept.  The full logits (rows x vocab x 4 bytes) never reach memory; what is written is
+// 8 bytes per row per column group.  A second small kernel merges the partials:
+//     logp[r] = logit[r, y_r] - (m + log sum_g s_g exp(m_g - m)).
+#include "gemm_core.h"
+#include "ssd_internal.h"
+
+namespace ssd {
+
+constexpr int LM_BM = 128, LM_BN = 128, LM_WM = 2, LM_WN = 2;
+constexpr int LM_WTN = LM_BN / LM_WN;          // columns per group
+
+int lmhead_col_groups(int vocab) { return vocab / LM_WTN; }
+
+// reduce over the 32 lanes that share a row set (same lane/32)
+template <class Op>
+__device__ __forceinline__ float row_allreduce32(float v, Op op) {
+    v = op(v, dpp_f<DPP_XOR1>(v));
+    v = op(v, dpp_f<DPP_XOR2>(v));
+    v = op(v, dpp_f<DPP_HALF_MIRROR>(v));
+    v = op(v, dpp_f<DPP_MIRROR>(v));
+    v = op(v, __shfl_xor(v, 16));
+    return v;
+}
+
+template <bool GREEDY>
+__global__ void __launch_bounds__(64 * LM_WM * LM_WN)
+lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,
+                   int Mv, int d, int vocab, float2* __restrict__ part_ms, float* __restrict__ tgt_logit,
+                   int2* __restrict__ part_arg, float descale) {
+    using Tile = GemmTile<LM_BM, LM_BN, LM_WM, LM_WN>;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tiles_m = (Mv + LM_BM - 1) / LM_BM;
+    // row tiles vary fastest: workgroups that run together share one slab of W_lm
+    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    f32x16_t acc[Tile::TM][Tile::TN];
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    Tile::run(hv, w_lm, Mv, d, tm * LM_BM, tn * LM_BN, reinterpret_cast<f16_t*>(smem_raw), acc);
+
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / LM_WN, wn = wave % LM_WN;
+    const int row0 = tm * LM_BM + wm * Tile::WTM, col0 = tn * LM_BN + wn * Tile::WTN;
+    const int group = col0 / LM_WTN;
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] *= descale;
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + acc_row(i, r, lane);
+            const bool live = row < Mv;
+            float mx = -INFINITY;
+            int best_c = 0;
+#pragma unroll
+            for (int j = 0; j < Tile::TN; ++j) {
+                const float v = acc[i][j][r];
+                if (v > mx) { mx = v; best_c = col0 + acc_col(j, lane); }
+            }
+            const float m = row_allreduce32(mx, OpMax());
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < Tile::TN; ++j) s += __expf(acc[i][j][r] - m);
+            s = row_allreduce32(s, OpSum());
+            if (live) {
+                int tgt = targets[row];
+                tgt = tgt < 0 ? 0 : (tgt >= vocab ? vocab - 1 : tgt);
+                const int rel = tgt - col0 - lane % 32;
+                if (rel >= 0 && rel < Tile::WTN && rel % 32 == 0) {
+#pragma unroll
+                    for (int j = 0; j < Tile::TN; ++j)
+                        if (rel == j * 32) tgt_logit[row] = acc[i][j][r];
+                }
+                if (lane % 32 == 0) part_ms[(int64_t)group * Mv + row] = make_float2(m, s);
+            }
+            if (GREEDY) {
+                // lowest column among the lanes that hold the row maximum
+                int cand = (mx == m) ? best_c : 0x7fffffff;
+                cand = min(cand, dpp_i<DPP_XOR1>(cand));
+                cand = min(cand, dpp_i<DPP_XOR2>(cand));
+                cand = min(cand, dpp_i<DPP_HALF_MIRROR>(cand));
+                cand = min(cand, dpp_i<DPP_MIRROR>(cand));
+                cand = min(cand, __shfl_xor(cand, 16));
+                if (live && lane % 32 == 0) part_arg[(int64_t)group * Mv + row] = make_int2(__float_as_int(m), cand);
+            }
+        }
+}
+
+void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+                        float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
+                        hipStream_t st) {
+    if (Mv <= 0) return;
+    constexpr size_t lds = gemm_lds_bytes<LM_BM, LM_BN>();
+    const int tiles = ((Mv + LM_BM - 1) / LM_BM) * (vocab / LM_BN);
+    if (want_greedy)
+        hipLaunchKernelGGL(lmhead_mfma_kernel<true>, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
+                           Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
+    else
+        hipLaunchKernelGGL(lmhead_mfma_kernel<false>, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
+                           Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
+}
+
+// One wavefront per row merges the per-group partials.
+__global__ void __launch_bounds__(256) lmhead_finalize_kernel(const float2* __restrict__ part_ms,
+                                                              const float* __restrict__ tgt_logit,
+                                                              const int2* __restrict__ part_arg, int n_groups, int Mv,
+                                                              float* __restrict__ logp, int32_t* __restrict__ greedy) {
+    const int lane = threadIdx.x % 64;
+    const int row = blockIdx.x * 4 + threadIdx.x / 64;
+    if (row >= Mv) return;
+    float m = -INFINITY, s = 0.f;
+    for (int g = lane; g < n_groups; g += 64) {
+        const float2 p = part_ms[(int64_t)g * Mv + row];
+        if (p.x > m) { s = s * __expf(m - p.x) + p.y; m = p.x; } else { s += p.y * __expf(p.x - m); }
+    }
+    const float M = group_allreduce<64>(m, OpMax());
+    s = (m == -INFINITY) ? 0.f : s * __expf(m - M);
+    const float S = group_allreduce<64>(s, OpSum());
+    if (lane == 0) logp[row] = tgt_logit[row] - (M + logf(S));
+    if (greedy) {
+        int cand = 0x7fffffff;
+        for (int g = lane; g < n_groups; g += 64) {
+            const int2 a = part_arg[(int64_t)g * Mv + row];
+            if (__int_as_float(a.x) == M && a.y < cand) cand = a.y;
+        }
+        cand = group_allreduce_i<64>(cand, OpMinI());
+        if (lane == 0) greedy[row] = cand;
+    }
+}
+
+void launch_lmhead_finalize(const float2* part_ms, const float* tgt_logit, const int2* part_arg, int n_groups, int Mv,
+                            float* logp, int32_t* greedy, hipStream_t st) {
+    if (Mv <= 0) return;
+    hipLaunchKernelGGL(lmhead_finalize_kernel, dim3((Mv + 3) / 4), dim3(256), 0, st, part_ms, tgt_logit, part_arg,
+                       n_groups, Mv, logp, greedy);
+}
+
+}  // namespace ssd

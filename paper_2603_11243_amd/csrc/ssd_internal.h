@@ -1,0 +1,84 @@
+// Internal declarations shared by the kernel files and the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/ssd.h"
+
+namespace ssd {
+
+// ---- gate.hip
+void launch_gate(const void* logits, int dtype, int64_t n_rows, int V, const int32_t* cu_frames_dev, int B,
+                 int blank, float tau, float* H, int32_t* arg, float* max_entropy, uint8_t* gate_pass,
+                 int32_t* draft, int32_t* draft_len, hipStream_t st);
+
+// ---- row metadata built on the host for one verify_forward call
+// src code of a decoder row: speech rows hold the speech_emb row index; token rows hold
+// SRC_PROMPT | index into prompt_ids or SRC_DRAFT | index into draft_ids.
+constexpr int32_t SRC_PROMPT = 0x40000000;
+constexpr int32_t SRC_DRAFT = (int32_t)0x80000000u;
+constexpr int32_t SRC_MASK = 0x3fffffff;
+
+// One attention work item: a tile of query rows of one utterance.
+struct AttnTile {
+    int32_t seq_start;   // first decoder row of the utterance
+    int32_t seq_len;     // rows in the utterance
+    int32_t q_start;     // first query position of this tile (multiple of the tile height)
+    int32_t pad;
+};
+
+// ---- elementwise.hip
+void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
+                       const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
+                       hipStream_t st);
+// a = rmsnorm(x) * gain;  rows optionally gathered through row_idx (NULL = identity)
+void launch_rmsnorm(int dtype, const float* x, const void* gain, const int32_t* row_idx, int n_rows, int d,
+                    float eps, void* out, hipStream_t st);
+
+// ---- f32_path.hip (all-fp32 decoder for the tiny configuration)
+enum F32Epilogue { F32_STORE = 0, F32_ADD = 1 };
+void launch_gemm_f32(const float* A, const float* W, float* C, int M, int N, int K, int epilogue, hipStream_t st);
+void launch_rope_f32(float* qkv, const int32_t* pos, const float* rope_tab, int M, int n_heads_rot, int head_dim,
+                     int row_stride, hipStream_t st);
+void launch_swiglu_f32(const float* gu, float* h, int M, int d_ff, hipStream_t st);
+void launch_attn_f32(const float* qkv, float* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
+                     int n_kv_heads, int head_dim, hipStream_t st);
+void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+                       float* logp, int32_t* greedy, hipStream_t st);
+
+// ---- gemm_mfma.hip (f16 MFMA GEMMs with fused epilogues), attn_mfma.hip, lmhead_mfma.hip.
+// Activations and converted weights are IEEE half bit patterns; `descale` undoes the weight scale.
+void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
+                          const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
+                          hipStream_t st);
+void launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, int M, int N, int K, float descale,
+                          hipStream_t st);
+void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
+                        float descale, hipStream_t st);
+void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
+                      int n_kv_heads, hipStream_t st);
+// partial log-sum-exp of the LM head over column groups; see lmhead_mfma.hip
+int lmhead_col_groups(int vocab);
+void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d,
+                        int vocab, float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy,
+                        float descale, hipStream_t st);
+void launch_lmhead_finalize(const float2* part_ms, const float* tgt_logit, const int2* part_arg, int n_groups,
+                            int Mv, float* logp, int32_t* greedy, hipStream_t st);
+
+// weight re-layout at context creation
+// (bf16 weights are converted to f16 times the power of two `scale`; fp32 weights are copied)
+void launch_absmax(int dtype, const void* w, int64_t n, unsigned int* out_bits, hipStream_t st);
+void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, hipStream_t st);
+void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, void* out, int d_q, int d_kv,
+                     int d_model, int head_dim, float scale, hipStream_t st);
+void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
+                         hipStream_t st);
+
+// ---- accept (shared by both dtypes): first failing token per utterance
+void launch_accept_scan(const float* logp, const int32_t* cu_draft_dev, int Bv, float ln_tau, int32_t* accept_len,
+                        uint8_t* all_accepted, hipStream_t st);
+
+}  // namespace ssd

