@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the gate -> verify -> accept hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A step is one pass of the whole path over one synthetic batch that is already resident in HBM:
+ctc_gate -> (read gate flags and draft lengths, map CTC ids to LLM ids: the caller's glue) ->
+verify_forward -> accept_prefix.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from workloads import (WORKLOADS, make_ctc_batch, make_ctc_to_llm_map, make_model_weights,  # noqa: E402
+                       make_verify_inputs)
+
+PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense 16-bit matrix peak (bf16 and fp16)
+PEAK_HBM_GBS = 8000.0
+
+
+def layer_gemm_flops(m, M):
+    """2 * M * (parameters of the projection matrices of one layer)."""
+    return 2.0 * M * m.params_per_layer()
+
+
+class Step:
+    """Everything one step needs, prepared once; `run()` enqueues one step and returns its outputs."""
+
+    def __init__(self, wl, ctx, device):
+        from paper_2603_11243_amd.binding import Context  # noqa: F401
+        self.wl, self.ctx = wl, ctx
+        self.cb = make_ctc_batch(wl)
+        self.logits = self.cb.logits.to(device)
+        self.table = torch.from_numpy(make_ctc_to_llm_map(wl)).to(device)
+        self.cu_frames = self.cb.cu_frames
+        B, n_frames = wl.B, int(self.cu_frames[-1])
+        # Inputs of the verify pass exist for every utterance; a step uses those of the utterances
+        # that fail the gate.  Speech rows: round(6 * seconds) (or the fixed count), prompt ids random.
+        self.vi_all = make_verify_inputs(wl, self.cb.seconds, [np.zeros(0, np.int32)] * B, device=device)
+        self.prompt_ids = torch.from_numpy(self.vi_all.prompt_ids).to(device)
+        self.gate_out = None
+        max_tok = int(self.vi_all.cu_speech[-1] + self.vi_all.cu_prompt[-1]) + n_frames      # a draft is at most T tokens
+        ctx.reserve(max_frames=n_frames, max_tokens=max_tok, max_verify_rows=n_frames, max_utts=B)
+        self.device = device
+        self.frame_off = torch.from_numpy(self.cu_frames[:-1].astype(np.int64)).to(device)
+
+    def run(self, tau_slm):
+        wl, ctx, vi = self.wl, self.ctx, self.vi_all
+        g = ctx.ctc_gate(self.logits, self.cu_frames, wl.blank_id, wl.tau_ctc, out=self.gate_out)
+        self.gate_out = g
+        # ---- caller's glue: which utterances go on, how long their drafts are, CTC id -> LLM id
+        flags = torch.stack([g["gate_pass"].to(torch.int32), g["draft_len"]]).cpu().numpy()   # one D2H sync
+        fail = np.flatnonzero(flags[0] == 0)
+        if len(fail) == 0:
+            return g, None, None, 0
+        U = flags[1][fail]
+        cu_d = np.zeros(len(fail) + 1, np.int32); cu_d[1:] = np.cumsum(U)
+        S = np.diff(vi.cu_speech)[fail]; P = np.diff(vi.cu_prompt)[fail]
+        cu_s = np.zeros(len(fail) + 1, np.int32); cu_s[1:] = np.cumsum(S)
+        cu_p = np.zeros(len(fail) + 1, np.int32); cu_p[1:] = np.cumsum(P)
+        # gather index of the draft tokens inside draft_ctc, and of the speech / prompt rows
+        starts = self.cu_frames[:-1][fail].astype(np.int64)
+        idx = np.repeat(starts - cu_d[:-1], U) + np.arange(int(cu_d[-1]))
+        draft_ids = self.table[g["draft_ctc"][torch.from_numpy(idx).to(self.device)].long()].to(torch.int32)
+        if len(fail) == wl.B:
+            speech, prompt = vi.speech_emb, self.prompt_ids
+        else:
+            sidx = np.repeat(vi.cu_speech[:-1][fail].astype(np.int64) - cu_s[:-1], S) + np.arange(int(cu_s[-1]))
+            pidx = np.repeat(vi.cu_prompt[:-1][fail].astype(np.int64) - cu_p[:-1], P) + np.arange(int(cu_p[-1]))
+            speech = vi.speech_emb[torch.from_numpy(sidx).to(self.device)]
+            prompt = self.prompt_ids[torch.from_numpy(pidx).to(self.device)]
+        hv = ctx.verify_forward(speech, cu_s, prompt, cu_p, draft_ids, cu_d)
+        acc = ctx.accept_prefix(hv, draft_ids, cu_d, tau_slm)
+        meta = {"fail": fail, "cu_s": cu_s, "cu_p": cu_p, "cu_d": cu_d, "speech": speech, "prompt": prompt,
+                "draft_ids": draft_ids}
+        return g, acc, meta, int(cu_d[-1])
+
+
+def tau_for(wl, q=1.9):
+    s = 0.02 * np.sqrt(wl.model.d_model)
+    return float(np.exp(-np.log(wl.model.vocab) - s * s / 2 - q * s))
+
+
+def cpu_baseline(wl, step, weights, meta, budget_tokens):
+    """The oracle, as it stands, on this machine's host cores, over a bounded sample of the same batch."""
+    from oracle import ssd_oracle as O
+    import threadpoolctl
+    cores = max((p["num_threads"] for p in threadpoolctl.threadpool_info() if p.get("user_api") == "blas"), default=1)
+    fail = meta["fail"]
+    lens = np.diff(meta["cu_s"]) + np.diff(meta["cu_p"]) + np.diff(meta["cu_d"])
+    order = np.argsort(-lens)
+    pick, tok = [], 0
+    for k in order[len(order) // 2:]:                       # start from median-length utterances
+        if tok + lens[k] > budget_tokens and pick:
+            break
+        pick.append(int(k)); tok += int(lens[k])
+    # host copies, widened outside the timed region (the oracle's arithmetic is what is timed)
+    w64 = {"embed": weights["embed"].double().cpu(), "lm_head": weights["lm_head"].double().cpu(),
+           "norm_final": weights["norm_final"].double().cpu(),
+           "layers": [{k: v.double().cpu() for k, v in L.items()} for L in weights["layers"]]}
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    sp = torch.cat([meta["speech"][meta["cu_s"][k]:meta["cu_s"][k + 1]] for k in pick]).double().cpu()
+    pr = np.concatenate([meta["prompt"][meta["cu_p"][k]:meta["cu_p"][k + 1]].cpu().numpy() for k in pick])
+    dr = np.concatenate([meta["draft_ids"][meta["cu_d"][k]:meta["cu_d"][k + 1]].cpu().numpy() for k in pick])
+    cs, cp, cd = (cu(np.diff(meta[n])[pick]) for n in ("cu_s", "cu_p", "cu_d"))
+    utt = fail[pick]
+    rows = np.concatenate([np.arange(step.cu_frames[b], step.cu_frames[b + 1]) for b in utt])
+    z = step.cb.logits[rows].float().numpy()
+    cuf = cu([step.cu_frames[b + 1] - step.cu_frames[b] for b in utt])
+    t0 = time.perf_counter()
+    O.ctc_gate(z, cuf, wl.blank_id, wl.tau_ctc)
+    lp = O.draft_logp(w64, wl.model, sp, cs, pr, cp, dr, cd)
+    for x in lp:
+        O.accept_prefix(x, tau_for(wl))
+    dt = time.perf_counter() - t0
+    n_draft = int(cd[-1])
+    return {"value": n_draft / dt, "unit": "verified draft tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(pick)} of {len(fail)} verified utterances ({n_draft} draft tokens, {tok} decoder rows), "
+                      f"gate+verify+accept in float64 numpy, {dt:.1f} s",
+            "utterances_per_s": len(pick) / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3_1b_ragged64", choices=list(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-tokens", type=int, default=3000)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (utterance-sharded data parallelism needs no collectives and is "
+              "not built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    from paper_2603_11243_amd.binding import Context
+    device = torch.device("cuda:0")
+    wl = WORKLOADS[args.workload]
+    m = wl.model
+    weights = make_model_weights(m, wl.seed, device=device)
+    ctx = Context(m, weights, device=device)
+    step = Step(wl, ctx, device)
+    tau = tau_for(wl)
+
+    for _ in range(max(args.warmup, 1)):
+        g, acc, meta, n_draft = step.run(tau)
+    torch.cuda.synchronize()
+    ctx.profile_select("gemm_gate_up")              # time the dominant kernel with HIP events, live
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g, acc, meta, n_draft = step.run(tau)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dom_ms, dom_n = ctx.profile_read()["gemm_gate_up"]
+
+    # per-class breakdown in one extra, untimed step
+    ctx.profile_select(-1)
+    step.run(tau)
+    breakdown = {k: round(v[0], 4) for k, v in ctx.profile_read().items()}
+    ctx.profile_select(-2)
+    # verify+accept alone (metric (i) of the workload definition)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        hv = ctx.verify_forward(meta["speech"], meta["cu_s"], meta["prompt"], meta["cu_p"], meta["draft_ids"], meta["cu_d"])
+        ctx.accept_prefix(hv, meta["draft_ids"], meta["cu_d"], tau)
+    torch.cuda.synchronize()
+    dt_va = time.perf_counter() - t1
+
+    ms_per_step = dt / args.steps * 1e3
+    M = int(meta["cu_s"][-1] + meta["cu_p"][-1] + meta["cu_d"][-1])
+    Bv = len(meta["fail"])
+    gate_up_flops = 2.0 * M * m.d_model * 2 * m.d_ff
+    avg_ms = dom_ms / max(dom_n, 1)
+    achieved = gate_up_flops / (avg_ms * 1e-3) / 1e12 if dom_n else 0.0
+    gemm_ms = sum(breakdown[k] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down"))
+    acc_len = acc["accept_len"].cpu().numpy()
+    out = {
+        "metric": "verified draft tokens/s (gate+verify+accept, whole step)",
+        "value": n_draft / (dt / args.steps), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 MFMA operands (bf16-stored weights converted exactly), fp32 accumulate/residual",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "utterances": wl.B, "verified_utterances": Bv, "decoder_rows": M,
+                   "draft_tokens": n_draft, "ctc_frames": int(step.cu_frames[-1]), "V_ctc": wl.V_ctc,
+                   "layers": m.n_layers, "d_model": m.d_model, "vocab": m.vocab},
+        "utterances_per_s": wl.B / (dt / args.steps),
+        "verify_accept_tokens_per_s": n_draft / (dt_va / args.steps),
+        "gate_pass_rate": float(g["gate_pass"].float().mean().cpu()),
+        "full_accept_rate": float(acc["all_accepted"].float().mean().cpu()),
+        "mean_accepted_prefix_frac": float(np.mean(acc_len / np.maximum(np.diff(meta["cu_d"]), 1))),
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel<EpiSwiglu> (gate/up projection + SiLU*mul)",
+                     "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_MFMA_TFLOPS, "traffic": None,
+                     "avg_launch_ms": avg_ms, "launches_timed": dom_n, "flops_per_launch": gate_up_flops},
+        "breakdown_ms_per_step": breakdown,
+        "all_projection_gemms": {"tflops": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
+                                 "frac_of_peak": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

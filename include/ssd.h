@@ -99,6 +99,23 @@ int ssd_set_workspace(ssd_ctx *ctx, void *dev_ptr, size_t bytes);
 
 const char *ssd_last_error(const ssd_ctx *ctx);
 
+/* Measurement aid (no counterpart in the paper): times kernel launches with HIP events recorded on
+ * the context's stream.  ssd_profile_select chooses what the following calls bracket: one class,
+ * SSD_PROF_ALL, or SSD_PROF_OFF (default; no events are recorded).  It waits for the stream and
+ * discards earlier samples.  ssd_profile_read waits for the stream, writes per class the summed
+ * device time in milliseconds and the number of bracketed launches since the last select/read
+ * (arrays of SSD_PROF_N_CLASSES entries, host memory), and clears the samples.  A span covers one
+ * kernel launch, except SSD_PROF_GATE (the two gate kernels) and SSD_PROF_LMHEAD (LM head,
+ * merge of partials and prefix scan). */
+enum ssd_prof_class {
+    SSD_PROF_OFF = -2, SSD_PROF_ALL = -1,
+    SSD_PROF_GATE = 0, SSD_PROF_GEMM_QKV = 1, SSD_PROF_ATTN = 2, SSD_PROF_GEMM_O = 3,
+    SSD_PROF_GEMM_GATE_UP = 4, SSD_PROF_GEMM_DOWN = 5, SSD_PROF_LMHEAD = 6, SSD_PROF_OTHER = 7,
+    SSD_PROF_N_CLASSES = 8
+};
+int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
+int ssd_profile_read(ssd_ctx *ctx, float *total_ms /*host [8]*/, int32_t *launches /*host [8]*/);
+
 /* Sec. 2.1.  For every frame t of every utterance: softmax over the V_ctc scores (blank included),
  * entropy H_t in nats (Eq. 3, left side) and greedy label a_t = lowest-index argmax of the stored
  * scores (Eq. 2).  Per utterance b (frames cu_frames[b] .. cu_frames[b+1]-1, at least one):

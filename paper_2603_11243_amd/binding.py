@@ -18,7 +18,10 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
            -5: "SSD_EUNSUPPORTED"}
 
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
-           "ctc_gate", "verify_forward", "accept_prefix"]
+           "ssd_profile_select", "ssd_profile_read", "ctc_gate", "verify_forward", "accept_prefix"]
+
+PROF_OFF, PROF_ALL = -2, -1
+PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other"]
 
 
 class SsdError(RuntimeError):
@@ -57,6 +60,10 @@ def load_library() -> C.CDLL:
     lib.ssd_set_workspace.restype = i32
     lib.ssd_last_error.argtypes = [vp]
     lib.ssd_last_error.restype = C.c_char_p
+    lib.ssd_profile_select.argtypes = [vp, i32]
+    lib.ssd_profile_select.restype = i32
+    lib.ssd_profile_read.argtypes = [vp, vp, vp]
+    lib.ssd_profile_read.restype = i32
     lib.ctc_gate.argtypes = [vp, vp, i32, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.ctc_gate.restype = i32
     lib.verify_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
@@ -159,6 +166,16 @@ class Context:
     def set_workspace(self, buf: Optional[torch.Tensor]):
         self._ws = buf
         self._check(self._lib.ssd_set_workspace(self._h, _ptr(buf), 0 if buf is None else buf.numel()))
+
+    def profile_select(self, kernel_class):
+        k = PROF_CLASSES.index(kernel_class) if isinstance(kernel_class, str) else kernel_class
+        self._check(self._lib.ssd_profile_select(self._h, k))
+
+    def profile_read(self) -> dict:
+        ms = np.zeros(len(PROF_CLASSES), dtype=np.float32)
+        n = np.zeros(len(PROF_CLASSES), dtype=np.int32)
+        self._check(self._lib.ssd_profile_read(self._h, ms.ctypes.data, n.ctypes.data))
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(PROF_CLASSES)}
 
     # ---- the three calls -------------------------------------------------------------------
 

@@ -51,6 +51,29 @@ struct Stager {
     }
 };
 
+// Optional per-kernel-class timing with HIP events on the context's stream.
+struct Profiler {
+    int selected = SSD_PROF_OFF;               // SSD_PROF_OFF, SSD_PROF_ALL or one class
+    std::vector<hipEvent_t> pool;
+    struct Span { int cls; int e0, e1; };
+    std::vector<Span> spans;
+    int next_event = 0;
+    bool wants(int cls) const { return selected == SSD_PROF_ALL || selected == cls; }
+    int event(hipStream_t st) {
+        if (next_event == (int)pool.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return -1;
+            pool.push_back(e);
+        }
+        if (hipEventRecord(pool[next_event], st) != hipSuccess) return -1;
+        return next_event++;
+    }
+    void release() {
+        for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+        pool.clear(); spans.clear(); next_event = 0;
+    }
+};
+
 }  // namespace
 
 struct ssd_ctx {
@@ -71,6 +94,7 @@ struct ssd_ctx {
     size_t ws_bytes = 0;
     std::string err;
     Stager stager;
+    Profiler prof;
 };
 
 namespace {
@@ -113,6 +137,18 @@ int upload(ssd_ctx* c, const void* host, void* dev, size_t bytes) {
     HIP_TRY(c, c->stager.commit(slot, c->stream));
     return SSD_OK;
 }
+
+// Brackets the launches issued during its lifetime with two events when the class is being timed.
+struct ProfScope {
+    ssd_ctx* c; int cls; int e0 = -1;
+    ProfScope(ssd_ctx* ctx, int k) : c(ctx), cls(k) { if (c->prof.wants(cls)) e0 = c->prof.event(c->stream); }
+    ~ProfScope() {
+        if (e0 >= 0) {
+            const int e1 = c->prof.event(c->stream);
+            if (e1 >= 0) c->prof.spans.push_back({cls, e0, e1});
+        }
+    }
+};
 
 struct GatePlan { size_t H, arg, cu, total; };
 GatePlan plan_gate(int64_t frames, int64_t utts) {
@@ -310,6 +346,7 @@ void ssd_destroy(ssd_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     for (void* p : c->owned) if (p) (void)hipFree(p);
     c->stager.release();
+    c->prof.release();
     delete c;
 }
 
@@ -330,6 +367,31 @@ int ssd_set_workspace(ssd_ctx* ctx, void* dev_ptr, size_t bytes) {
     if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return fail(ctx, SSD_EINVAL, "workspace must be 256-byte aligned");
     ctx->ws = dev_ptr;
     ctx->ws_bytes = bytes;
+    return SSD_OK;
+}
+
+int ssd_profile_select(ssd_ctx* ctx, int kernel_class) {
+    if (!ctx) return SSD_EINVAL;
+    if (kernel_class < SSD_PROF_OFF || kernel_class >= SSD_PROF_N_CLASSES) return fail(ctx, SSD_EINVAL, "ssd_profile_select: unknown class %d", kernel_class);
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->prof.selected = kernel_class;
+    ctx->prof.spans.clear();
+    ctx->prof.next_event = 0;
+    return SSD_OK;
+}
+
+int ssd_profile_read(ssd_ctx* ctx, float* total_ms, int32_t* launches) {
+    if (!ctx || !total_ms || !launches) return SSD_EINVAL;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (int k = 0; k < SSD_PROF_N_CLASSES; ++k) { total_ms[k] = 0.f; launches[k] = 0; }
+    for (const Profiler::Span& sp : ctx->prof.spans) {
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof.pool[sp.e0], ctx->prof.pool[sp.e1]));
+        total_ms[sp.cls] += ms;
+        launches[sp.cls] += 1;
+    }
+    ctx->prof.spans.clear();
+    ctx->prof.next_event = 0;
     return SSD_OK;
 }
 
@@ -355,8 +417,11 @@ int ctc_gate(ssd_ctx* ctx, const void* logits, int dtype, const int32_t* cu_fram
     int32_t* cu_dev = reinterpret_cast<int32_t*>(ws + p.cu);
     int rc = upload(ctx, cu_frames, cu_dev, (size_t)(B + 1) * 4);
     if (rc != SSD_OK) return rc;
-    launch_gate(logits, dtype, n_rows, V_ctc, cu_dev, B, blank_id, tau_ctc, H, arg, max_entropy, gate_pass, draft_ctc,
-                draft_len, ctx->stream);
+    {
+        ProfScope ps(ctx, SSD_PROF_GATE);
+        launch_gate(logits, dtype, n_rows, V_ctc, cu_dev, B, blank_id, tau_ctc, H, arg, max_entropy, gate_pass, draft_ctc,
+                    draft_len, ctx->stream);
+    }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }
@@ -420,16 +485,16 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
     hipStream_t st = ctx->stream;
     const int Mi = (int)M, d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
 
-    launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, st);
+    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, st); }
     for (int l = 0; l < m.n_layers; ++l) {
-        launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, st);
+        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, st); }
         if (m.dtype == SSD_BF16) {
-            launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st);
-            launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st);
-            launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, Mi, d, dq, ctx->ds_o[l], st);
-            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st);
-            launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Mi, m.d_ff, d, ctx->ds_gu[l], st);
-            launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, Mi, d, m.d_ff, ctx->ds_down[l], st);
+            { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_O); launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, Mi, d, dq, ctx->ds_o[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Mi, m.d_ff, d, ctx->ds_gu[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, Mi, d, m.d_ff, ctx->ds_down[l], st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
@@ -443,7 +508,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
         }
     }
     // verification rows only: final RMSNorm of the positions that score a draft token
-    launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, st);
+    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, st); }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }
@@ -467,6 +532,7 @@ int accept_prefix(ssd_ctx* ctx, const void* h_verify, const int32_t* draft_ids, 
     int rc = upload(ctx, cu_draft, cu_dev, (size_t)(Bv + 1) * 4);
     if (rc != SSD_OK) return rc;
     hipStream_t st = ctx->stream;
+    ProfScope ps_all(ctx, SSD_PROF_LMHEAD);
     if (m.dtype == SSD_BF16) {
         float2* part_ms = reinterpret_cast<float2*>(ws + p.part_ms);
         float* tgt = reinterpret_cast<float*>(ws + p.tgt);
