@@ -212,8 +212,9 @@ int check_model(ssd_ctx* c, const ssd_model_cfg& m) {
     const int dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
     if (m.dtype == SSD_BF16) {
         if (m.head_dim != 128) return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs head_dim 128 (got %d)", m.head_dim);
-        if (m.d_model % 128 || m.d_ff % 128 || dq % 128 || dkv % 128 || m.vocab % 128)
-            return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs d_model, d_ff, head widths and vocab to be multiples of 128");
+        if (m.d_model % 256 || m.d_ff % 128 || dq % 128 || dkv % 128 || (dq + 2 * dkv) % 256 || m.vocab % 256)
+            return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs d_model, n_q_heads*head_dim + 2*n_kv_heads*head_dim and vocab to be "
+                                       "multiples of 256, d_ff a multiple of 128");
     } else if (m.dtype == SSD_F32) {
         if (m.head_dim % 4 || m.head_dim > 128) return fail(c, SSD_ESHAPE, "ssd_create: f32 needs head_dim %% 4 == 0 and <= 128");
         if (m.d_model % 16 || m.d_ff % 16 || dq % 16 || m.d_model > 1024)

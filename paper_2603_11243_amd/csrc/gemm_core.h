@@ -7,11 +7,16 @@
 // Lane l of a wavefront holds, for a 32x32 accumulator block, column l%32 and rows
 // 8*(r/4) + 4*(l/32) + r%4 for register r = 0..15.
 //
-// A workgroup of WAVES_M x WAVES_N wavefronts computes a BM x BN tile; K is consumed in slices of
-// BK = 64 staged through LDS (row stride padded to 72 elements so that the 16-byte fragment reads of
-// 32 consecutive rows fall on distinct banks).  Global loads of the next slice are issued before
-// the MFMAs of the current one.  Rows >= M are clamped on load and must be skipped by the epilogue.
-// Requirements: N % BN == 0, K % 64 == 0, A and W 16-byte aligned.
+// A workgroup of WAVES_M x WAVES_N wavefronts computes a BM x BN tile.  K is consumed in slices of
+// BK = 64 (128 bytes per row) that go from global memory straight into LDS with
+// buffer_load_dwordx4 ... lds (no register staging), double-buffered: the loads of slice k+1 are in
+// flight while the MFMAs of slice k run, one barrier per slice.
+// LDS layout of a slice: row-major, 128 bytes per row, the eight 16-byte chunks of row r stored at
+// chunk position c ^ (r & 7).  A load instruction fills 1 KB of LDS with lane i's 16 bytes at byte
+// 16*i, so lane i fetches the global chunk that belongs at that position; the fragment reads
+// (32 consecutive rows, same logical chunk) then touch eight different bank groups per 8 lanes.
+// Rows >= M are clamped on load and must be skipped by the epilogue.
+// Requirements: N % BN == 0, K % 64 == 0, A and W 16-byte aligned and smaller than 4 GiB.
 #pragma once
 #include "device_utils.h"
 
@@ -19,12 +24,13 @@ namespace ssd {
 
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void_t;
 
 constexpr int GEMM_BK = 64;
-constexpr int GEMM_LDS_STRIDE = GEMM_BK + 8;   // elements
+constexpr int GEMM_ROW_BYTES = GEMM_BK * 2;
 
 template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return (size_t)(BM + BN) * GEMM_LDS_STRIDE * 2; }
+constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * GEMM_ROW_BYTES; }
 
 __device__ __forceinline__ f16x8_t as_f16x8(const uint4& v) { return __builtin_bit_cast(f16x8_t, v); }
 
@@ -32,78 +38,93 @@ __device__ __forceinline__ f16x8_t as_f16x8(const uint4& v) { return __builtin_b
 __device__ __forceinline__ int acc_row(int i, int r, int lane) { return i * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4); }
 __device__ __forceinline__ int acc_col(int j, int lane) { return j * 32 + (lane % 32); }
 
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+    // raw buffer, no bounds (offsets are clamped by the caller), data format 32 bit
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0xffffffff, 0x00020000);
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 struct GemmTile {
-    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int WAVES = WAVES_M * WAVES_N;
+    static constexpr int NT = 64 * WAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
-    static constexpr int A_CHUNKS = BM * (GEMM_BK / 8) / NT;    // 16-byte chunks per thread per slice
-    static constexpr int B_CHUNKS = BN * (GEMM_BK / 8) / NT;
-    static_assert(BM * (GEMM_BK / 8) % NT == 0 && BN * (GEMM_BK / 8) % NT == 0, "tile/thread mismatch");
+    static constexpr int A_LOADS = BM / (8 * WAVES);     // 1 KB (8 rows) per wavefront load instruction
+    static constexpr int B_LOADS = BN / (8 * WAVES);
+    static constexpr int A_BYTES = BM * GEMM_ROW_BYTES, B_BYTES = BN * GEMM_ROW_BYTES;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile/thread mismatch");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
 
-    // acc must be zero-initialised by the caller.  smem: gemm_lds_bytes<BM,BN>() bytes.
+    // acc must be zero-initialised by the caller.  smem: gemm_lds_bytes<BM,BN>() bytes, 16-byte aligned.
     static __device__ __forceinline__ void run(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int K,
-                                               int m0, int n0, f16_t* smem, f32x16_t (&acc)[TM][TN]) {
-        f16_t* As = smem;
-        f16_t* Bs = smem + BM * GEMM_LDS_STRIDE;
-        const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+                                               int m0, int n0, unsigned char* smem, f32x16_t (&acc)[TM][TN]) {
+        const int tid = threadIdx.x, lane = tid % 64;
+        const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
         const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+        const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A), w_rsrc = make_rsrc(W);
 
-        const uint4* a_src[A_CHUNKS];
-        const uint4* b_src[B_CHUNKS];
-        int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
+        // ---- global -> LDS: byte offsets of this lane's chunk for every load instruction
+        // instruction i of this wavefront fills rows (i*WAVES + wave)*8 .. +7 of the slice
+        const int lrow = lane / 8, lslot = lane % 8;            // position inside the 1 KB block
+        unsigned a_off[A_LOADS], b_off[B_LOADS];
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int c = tid + i * NT, row = c / 8, kc = c % 8;
-            const int grow = min(m0 + row, M - 1);
-            a_src[i] = reinterpret_cast<const uint4*>(A + (int64_t)grow * K + kc * 8);
-            a_dst[i] = row * GEMM_LDS_STRIDE + kc * 8;
+        for (int i = 0; i < A_LOADS; ++i) {
+            const int r = (i * WAVES + wave) * 8 + lrow;
+            const int grow = min(m0 + r, M - 1);
+            a_off[i] = (unsigned)grow * (unsigned)K * 2u + (unsigned)((lslot ^ (r & 7)) * 16);
         }
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int c = tid + i * NT, row = c / 8, kc = c % 8;
-            b_src[i] = reinterpret_cast<const uint4*>(W + (int64_t)(n0 + row) * K + kc * 8);
-            b_dst[i] = row * GEMM_LDS_STRIDE + kc * 8;
+        for (int i = 0; i < B_LOADS; ++i) {
+            const int r = (i * WAVES + wave) * 8 + lrow;
+            b_off[i] = (unsigned)(n0 + r) * (unsigned)K * 2u + (unsigned)((lslot ^ (r & 7)) * 16);
         }
-        uint4 a_reg[A_CHUNKS], b_reg[B_CHUNKS];
+        auto issue_loads = [&](int kt, int stage) {
+            unsigned char* sa = smem + stage * STAGE_BYTES;
+            unsigned char* sb = sa + A_BYTES;
+            const int koff = kt * GEMM_ROW_BYTES;
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = a_src[i][0];
+            for (int i = 0; i < A_LOADS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void_t*)(sa + (i * WAVES + wave) * 1024), 16, a_off[i], koff, 0, 0);
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) b_reg[i] = b_src[i][0];
+            for (int i = 0; i < B_LOADS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void_t*)(sb + (i * WAVES + wave) * 1024), 16, b_off[i], koff, 0, 0);
+        };
 
-        const int a_frag = (wm * WTM + lane % 32) * GEMM_LDS_STRIDE + (lane / 32) * 8;
-        const int b_frag = (wn * WTN + lane % 32) * GEMM_LDS_STRIDE + (lane / 32) * 8;
+        // ---- LDS -> fragments: row = lane%32 (+32 per block), logical chunk = 2*kk + lane/32
+        int a_rd[GEMM_BK / 16], b_rd[GEMM_BK / 16];
+#pragma unroll
+        for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
+            const int slot = (2 * kk + lane / 32) ^ (lane & 7);
+            a_rd[kk] = (wm * WTM + lane % 32) * GEMM_ROW_BYTES + slot * 16;
+            b_rd[kk] = A_BYTES + (wn * WTN + lane % 32) * GEMM_ROW_BYTES + slot * 16;
+        }
+
         const int KT = K / GEMM_BK;
+        issue_loads(0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): slice 0 has landed in LDS
+        __syncthreads();
         for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-            for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4*>(As + a_dst[i]) = a_reg[i];
-#pragma unroll
-            for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<uint4*>(Bs + b_dst[i]) = b_reg[i];
-            __syncthreads();
-            if (kt + 1 < KT) {
-                const int off = (kt + 1) * (GEMM_BK / 8);     // in uint4 units
-#pragma unroll
-                for (int i = 0; i < A_CHUNKS; ++i) a_reg[i] = a_src[i][off];
-#pragma unroll
-                for (int i = 0; i < B_CHUNKS; ++i) b_reg[i] = b_src[i][off];
-            }
+            const int stage = kt & 1;
+            if (kt + 1 < KT) issue_loads(kt + 1, stage ^ 1);
+            const unsigned char* sbase = smem + stage * STAGE_BYTES;
 #pragma unroll
             for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
                 f16x8_t a[TM], b[TN];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    a[i] = as_f16x8(*reinterpret_cast<const uint4*>(As + a_frag + i * 32 * GEMM_LDS_STRIDE + kk * 16));
+                    a[i] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + a_rd[kk] + i * 32 * GEMM_ROW_BYTES));
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    b[j] = as_f16x8(*reinterpret_cast<const uint4*>(Bs + b_frag + j * 32 * GEMM_LDS_STRIDE + kk * 16));
+                    b[j] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + b_rd[kk] + j * 32 * GEMM_ROW_BYTES));
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
             }
-            __syncthreads();
+            __builtin_amdgcn_s_waitcnt(0x0F70);    // next slice landed (this wavefront's part)
+            __syncthreads();                       // everyone's part landed; everyone done reading `stage`
         }
     }
 };

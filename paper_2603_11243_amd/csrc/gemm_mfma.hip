@@ -116,7 +116,7 @@ gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M
         for (int j = 0; j < Tile::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile::run(A, W, M, K, tm * BM, tn * BN, reinterpret_cast<f16_t*>(smem_raw), acc);
+    Tile::run(A, W, M, K, tm * BM, tn * BN, smem_raw, acc);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
@@ -128,7 +128,7 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, con
     auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, Epi>;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
     static bool attr_set = false;
-    if (!attr_set && lds > 48 * 1024) {
+    if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
@@ -136,22 +136,30 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, con
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, epi);
 }
 
+// Tile choice: 256x256 with eight wavefronts (wave tile 128x64) when there are enough rows to fill
+// such tiles; 128x128 with four wavefronts otherwise (N is a multiple of 256 for every GEMM here).
+template <class Epi>
+static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M > 512) launch_gemm<256, 256, 2, 4>(A, W, M, N, K, epi, st);
+    else launch_gemm<128, 128, 2, 2>(A, W, M, N, K, epi, st);
+}
+
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale, hipStream_t st) {
     const int N = d_q + 2 * d_kv;
     EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab)};
-    launch_gemm<128, 128, 2, 2>(A, Wqkv_packed, M, N, d_model, epi, st);
+    launch_by_shape(A, Wqkv_packed, M, N, d_model, epi, st);
 }
 
 void launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, int M, int N, int K, float descale, hipStream_t st) {
     EpiResidual epi{x, N, descale};
-    launch_gemm<128, 128, 2, 2>(A, W, M, N, K, epi, st);
+    launch_by_shape(A, W, M, N, K, epi, st);
 }
 
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
                         float descale, hipStream_t st) {
     EpiSwiglu epi{h, d_ff, descale};
-    launch_gemm<128, 128, 2, 2>(A, Wgu_packed, M, 2 * d_ff, K, epi, st);
+    launch_by_shape(A, Wgu_packed, M, 2 * d_ff, K, epi, st);
 }
 
 }  // namespace ssd

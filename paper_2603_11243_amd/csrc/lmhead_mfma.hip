@@ -11,7 +11,7 @@
 
 namespace ssd {
 
-constexpr int LM_BM = 128, LM_BN = 128, LM_WM = 2, LM_WN = 2;
+constexpr int LM_BM = 256, LM_BN = 256, LM_WM = 2, LM_WN = 4;
 constexpr int LM_WTN = LM_BN / LM_WN;          // columns per group
 
 int lmhead_col_groups(int vocab) { return vocab / LM_WTN; }
@@ -44,7 +44,7 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
         for (int j = 0; j < Tile::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile::run(hv, w_lm, Mv, d, tm * LM_BM, tn * LM_BN, reinterpret_cast<f16_t*>(smem_raw), acc);
+    Tile::run(hv, w_lm, Mv, d, tm * LM_BM, tn * LM_BN, smem_raw, acc);
 
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / LM_WN, wn = wave % LM_WN;
@@ -98,17 +98,28 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
         }
 }
 
+template __global__ void lmhead_mfma_kernel<true>(const f16_t*, const f16_t*, const int32_t*, int, int, int, float2*, float*, int2*, float);
+template __global__ void lmhead_mfma_kernel<false>(const f16_t*, const f16_t*, const int32_t*, int, int, int, float2*, float*, int2*, float);
+
 void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                         float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
                         hipStream_t st) {
     if (Mv <= 0) return;
     constexpr size_t lds = gemm_lds_bytes<LM_BM, LM_BN>();
     const int tiles = ((Mv + LM_BM - 1) / LM_BM) * (vocab / LM_BN);
+    auto kern_greedy = lmhead_mfma_kernel<true>;
+    auto kern_plain = lmhead_mfma_kernel<false>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_greedy), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_plain), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
     if (want_greedy)
-        hipLaunchKernelGGL(lmhead_mfma_kernel<true>, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
+        hipLaunchKernelGGL(kern_greedy, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
                            Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
     else
-        hipLaunchKernelGGL(lmhead_mfma_kernel<false>, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
+        hipLaunchKernelGGL(kern_plain, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
                            Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
 }
 
