@@ -12,9 +12,11 @@
 // buffer_load_dwordx4 ... lds (no register staging), double-buffered: the loads of slice k+1 are in
 // flight while the MFMAs of slice k run, one barrier per slice.
 // LDS layout of a slice: row-major, 128 bytes per row, the eight 16-byte chunks of row r stored at
-// chunk position c ^ (r & 7).  A load instruction fills 1 KB of LDS with lane i's 16 bytes at byte
-// 16*i, so lane i fetches the global chunk that belongs at that position; the fragment reads
-// (32 consecutive rows, same logical chunk) then touch eight different bank groups per 8 lanes.
+// chunk position c ^ ((r >> 1) & 7).  A load instruction fills 1 KB of LDS with lane i's 16 bytes at
+// byte 16*i, so lane i fetches the global chunk that belongs at that position.  A fragment read
+// (consecutive rows, same logical chunk) then spreads every 16 lanes over all sixteen 16-byte
+// columns of the 256-byte LDS data path (measured: SQ_LDS_BANK_CONFLICT drops to zero; with
+// c ^ (r & 7) half of the LDS cycles were conflict cycles).
 // Rows >= M are clamped on load and must be skipped by the epilogue.
 // Requirements: N % BN == 0, K % 64 == 0, A and W 16-byte aligned and smaller than 4 GiB.
 #pragma once
@@ -72,12 +74,12 @@ struct GemmTile {
         for (int i = 0; i < A_LOADS; ++i) {
             const int r = (i * WAVES + wave) * 8 + lrow;
             const int grow = min(m0 + r, M - 1);
-            a_off[i] = (unsigned)grow * (unsigned)K * 2u + (unsigned)((lslot ^ (r & 7)) * 16);
+            a_off[i] = (unsigned)grow * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
         }
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
             const int r = (i * WAVES + wave) * 8 + lrow;
-            b_off[i] = (unsigned)(n0 + r) * (unsigned)K * 2u + (unsigned)((lslot ^ (r & 7)) * 16);
+            b_off[i] = (unsigned)(n0 + r) * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
         }
         auto issue_loads = [&](int kt, int stage) {
             unsigned char* sa = smem + stage * STAGE_BYTES;
@@ -95,36 +97,57 @@ struct GemmTile {
         int a_rd[GEMM_BK / 16], b_rd[GEMM_BK / 16];
 #pragma unroll
         for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
-            const int slot = (2 * kk + lane / 32) ^ (lane & 7);
+            const int slot = (2 * kk + lane / 32) ^ ((lane >> 1) & 7);
             a_rd[kk] = (wm * WTM + lane % 32) * GEMM_ROW_BYTES + slot * 16;
             b_rd[kk] = A_BYTES + (wn * WTN + lane % 32) * GEMM_ROW_BYTES + slot * 16;
         }
 
-        const int KT = K / GEMM_BK;
-        issue_loads(0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): slice 0 has landed in LDS
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int stage = kt & 1;
-            if (kt + 1 < KT) issue_loads(kt + 1, stage ^ 1);
+        auto read_frags = [&](int stage, int kk, f16x8_t (&a)[TM], f16x8_t (&b)[TN]) {
             const unsigned char* sbase = smem + stage * STAGE_BYTES;
 #pragma unroll
-            for (int kk = 0; kk < GEMM_BK / 16; ++kk) {
-                f16x8_t a[TM], b[TN];
+            for (int i = 0; i < TM; ++i)
+                a[i] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + a_rd[kk] + i * 32 * GEMM_ROW_BYTES));
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    a[i] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + a_rd[kk] + i * 32 * GEMM_ROW_BYTES));
+            for (int j = 0; j < TN; ++j)
+                b[j] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + b_rd[kk] + j * 32 * GEMM_ROW_BYTES));
+        };
+        auto mfma_block = [&](const f16x8_t (&a)[TM], const f16x8_t (&b)[TN]) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    b[j] = as_f16x8(*reinterpret_cast<const uint4*>(sbase + b_rd[kk] + j * 32 * GEMM_ROW_BYTES));
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-            }
-            __builtin_amdgcn_s_waitcnt(0x0F70);    // next slice landed (this wavefront's part)
-            __syncthreads();                       // everyone's part landed; everyone done reading `stage`
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+        };
+
+        // Software pipeline.  Invariant at the top of iteration kt: slice kt sits in stage kt&1 and
+        // its kk=0 fragments are in (a0, b0); the loads of slice kt+1 into the other stage are in
+        // flight.  The fragments of step kk+1 are read while the MFMAs of step kk run; the barrier
+        // that ends a slice sits between the last fragment read and the last MFMA block, so the
+        // first fragment read of the next slice and the global loads of the slice after it are
+        // issued before that MFMA block and overlap with it.
+        constexpr int KK = GEMM_BK / 16;
+        static_assert(KK == 4, "pipeline below is written for four k-steps per slice");
+        const int KT = K / GEMM_BK;
+        f16x8_t a0[TM], b0[TN], a1[TM], b1[TN];
+        issue_loads(0, 0);
+        if (KT > 1) issue_loads(1, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        read_frags(0, 0, a0, b0);
+        for (int kt = 0; kt < KT; ++kt) {
+            const int stage = kt & 1;
+            read_frags(stage, 1, a1, b1);
+            mfma_block(a0, b0);
+            read_frags(stage, 2, a0, b0);
+            mfma_block(a1, b1);
+            read_frags(stage, 3, a1, b1);
+            mfma_block(a0, b0);
+            // all reads of `stage` are issued; wait for them and for slice kt+1 (loaded during this slice)
+            __builtin_amdgcn_s_waitcnt(0x0070);    // vmcnt(0) lgkmcnt(0)
+            __syncthreads();
+            if (kt + 2 < KT) issue_loads(kt + 2, stage);
+            if (kt + 1 < KT) read_frags(stage ^ 1, 0, a0, b0);
+            mfma_block(a1, b1);
         }
     }
 };
