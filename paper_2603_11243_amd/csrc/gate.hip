@@ -109,6 +109,157 @@ __global__ void __launch_bounds__(256) gate_frames_vec(const T* __restrict__ log
     }
 }
 
+// bf16 fast path.  A bf16 score widened to fp32 has 16 zero bits at the bottom; the complement of
+// the element index is put there while widening (one v_lshl_or / v_and_or per element, the same
+// cost as the plain widening), so that ONE float maximum over these keys yields both the row maximum
+// (top 16 bits) and, among equal scores, the lowest index (largest complement) -- no per-element
+// compare/select.  That holds for a positive, normal maximum; rows whose maximum is negative, zero,
+// denormal or non-finite take the generic route (compare/select per element), chosen per
+// wavefront.  The second sweep is one fma (z*log2e - m*log2e), one v_exp_f32, one add, one fma per
+// element:  H = ln2 * (log2 S - W2/S) with S = sum 2^t, W2 = sum 2^t t, which is shift invariant
+// in t, so the rounding of m*log2e cancels.
+// The kernel is persistent (grid-stride over row blocks) so the per-lane index constants are built
+// once, and the loads of the next row block are issued before the arithmetic of the current one.
+__device__ __forceinline__ float max3_bits(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));   // returns an operand bit-exactly
+    return r;
+}
+__device__ __forceinline__ float max_bits(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+template <int W>
+__device__ __forceinline__ float group_max_bits(float v) {
+    v = max_bits(v, dpp_f<DPP_XOR1>(v));
+    v = max_bits(v, dpp_f<DPP_XOR2>(v));
+    v = max_bits(v, dpp_f<DPP_HALF_MIRROR>(v));
+    v = max_bits(v, dpp_f<DPP_MIRROR>(v));
+    if (W > 16) {
+        v = max_bits(v, __shfl_xor(v, 16));
+        v = max_bits(v, __shfl_xor(v, 32));
+    }
+    return v;
+}
+
+template <int LPR, int NCH>
+__global__ void __launch_bounds__(256) gate_frames_bf16_keyed(const bf16_t* __restrict__ logits, int64_t n_rows, int V,
+                                                              float* __restrict__ H_out, int32_t* __restrict__ arg_out) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+    const int g = threadIdx.x % LPR;
+    const int n_chunks = V / 8;
+    const int64_t n_blocks = (n_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    uint32_t low[NCH][8];                                  // (~index) & 0xffff of every element this lane owns
+#pragma unroll
+    for (int k = 0; k < NCH; ++k)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) low[k][e] = (~(uint32_t)((g + k * LPR) * 8 + e)) & 0xffffu;
+
+    auto load_block = [&](int64_t blk, u32x4 (&c)[NCH]) {
+        int64_t row = blk * ROWS_PER_BLOCK + threadIdx.x / LPR;
+        if (row >= n_rows) row = n_rows - 1;
+        const u32x4* src = reinterpret_cast<const u32x4*>(logits + row * (int64_t)V);
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            const int idx = g + k * LPR;
+            if (idx < n_chunks) c[k] = __builtin_nontemporal_load(src + idx);
+            else c[k] = (u32x4){0xf14af14au, 0xf14af14au, 0xf14af14au, 0xf14af14au};   // about -1e30: finite, exp -> 0
+        }
+    };
+
+    u32x4 cur[NCH], nxt[NCH];
+    int64_t blk = blockIdx.x;
+    if (blk < n_blocks) load_block(blk, cur);
+    for (; blk < n_blocks; blk += gridDim.x) {
+        const int64_t nblk = blk + gridDim.x;
+        if (nblk < n_blocks) load_block(nblk, nxt);
+        const int64_t row = blk * ROWS_PER_BLOCK + threadIdx.x / LPR;
+        const bool live = row < n_rows;
+
+        // ---- sweep 1: maximum of the keyed values
+        float mk = __uint_as_float(0xff800000u);           // -inf
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t x = cur[k][w];
+                const float k_lo = __uint_as_float((x << 16) | low[k][2 * w]);
+                const float k_hi = __uint_as_float((x & 0xffff0000u) | low[k][2 * w + 1]);
+                mk = max3_bits(mk, k_lo, k_hi);
+            }
+        mk = group_max_bits<LPR>(mk);
+        const uint32_t mb = __float_as_uint(mk);
+        const uint32_t expo = mb & 0x7f800000u;
+        const bool easy = (mb >> 31) == 0 && expo != 0 && expo != 0x7f800000u;
+        // generic route: plain maximum, then the lowest index that attains it by compare/select
+        auto generic_max = [&](float& m, int& arg) {
+            m = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < NCH; ++k)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) m = fmaxf(m, fmaxf(bf16_lo(cur[k][w]), bf16_hi(cur[k][w])));
+            m = group_allreduce<LPR>(m, OpMax());
+            arg = 0x7fffffff;
+#pragma unroll
+            for (int k = NCH - 1; k >= 0; --k)
+#pragma unroll
+                for (int w = 3; w >= 0; --w) {
+                    const int base = (g + k * LPR) * 8 + 2 * w;
+                    arg = (bf16_hi(cur[k][w]) == m) ? base + 1 : arg;
+                    arg = (bf16_lo(cur[k][w]) == m) ? base : arg;
+                }
+            arg = group_allreduce_i<LPR>(arg, OpMinI());
+        };
+        float m, S = 0.f, W2 = 0.f;
+        int arg;
+        if (__all(easy)) {
+            m = __uint_as_float(mb & 0xffff0000u);
+            arg = (int)((~mb) & 0xffffu);
+        } else {
+            generic_max(m, arg);
+        }
+        // ---- sweep 2: S = sum 2^t, W2 = sum 2^t t,  t = (z - m) log2(e) up to a row constant
+        float nml = -m * LOG2E;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float t0 = fmaf(bf16_lo(cur[k][w]), LOG2E, nml), t1 = fmaf(bf16_hi(cur[k][w]), LOG2E, nml);
+                const float e0 = __builtin_amdgcn_exp2f(t0), e1 = __builtin_amdgcn_exp2f(t1);
+                S += e0; W2 = fmaf(e0, t0, W2);
+                S += e1; W2 = fmaf(e1, t1, W2);
+            }
+        if (__any(W2 != W2)) {
+            // A score of -inf gives 0 * -inf above (and a non-number key in sweep 1): redo the rows of
+            // this wavefront on the generic route, with such terms counted as 0.
+            generic_max(m, arg);
+            nml = -m * LOG2E;
+            S = 0.f; W2 = 0.f;
+#pragma unroll
+            for (int k = 0; k < NCH; ++k)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float t0 = fmaxf(fmaf(bf16_lo(cur[k][w]), LOG2E, nml), -1e30f);
+                    const float t1 = fmaxf(fmaf(bf16_hi(cur[k][w]), LOG2E, nml), -1e30f);
+                    const float e0 = __builtin_amdgcn_exp2f(t0), e1 = __builtin_amdgcn_exp2f(t1);
+                    S += e0; W2 = fmaf(e0, t0, W2);
+                    S += e1; W2 = fmaf(e1, t1, W2);
+                }
+        }
+        S = group_allreduce<LPR>(S, OpSum());
+        W2 = group_allreduce<LPR>(W2, OpSum());
+        if (live && g == 0) {
+            H_out[row] = LN2 * (__builtin_amdgcn_logf(S) - W2 / S);
+            arg_out[row] = arg;
+        }
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) cur[k] = nxt[k];
+    }
+}
+
 // Any V, any alignment: one wavefront per row, two passes over memory (second pass hits cache).
 template <typename T>
 __global__ void __launch_bounds__(256) gate_frames_generic(const T* __restrict__ logits, int64_t n_rows,
@@ -198,6 +349,16 @@ static void launch_vec(const T* logits, int64_t n_rows, int V, float* H, int32_t
     const int n_chunks = V / Chunk<T>::N;
     const int nch = (n_chunks + LPR - 1) / LPR;
     const unsigned grid = (unsigned)((n_rows + (256 / LPR) - 1) / (256 / LPR));
+    if constexpr (sizeof(T) == 2) {
+        // persistent launch: enough workgroups to fill 256 CUs several times over, no more than there is work
+        const unsigned pgrid = grid < 256u * 8u ? grid : 256u * 8u;
+        const bf16_t* z = logits;
+        if (nch <= 1) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 1>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
+        else if (nch <= 2) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 2>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
+        else if (nch <= 4) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 4>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
+        else hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 8>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
+        return;
+    }
     if (nch <= 1) hipLaunchKernelGGL((gate_frames_vec<T, LPR, 1>), dim3(grid), dim3(256), 0, st, logits, n_rows, V, H, arg);
     else if (nch <= 2) hipLaunchKernelGGL((gate_frames_vec<T, LPR, 2>), dim3(grid), dim3(256), 0, st, logits, n_rows, V, H, arg);
     else if (nch <= 4) hipLaunchKernelGGL((gate_frames_vec<T, LPR, 4>), dim3(grid), dim3(256), 0, st, logits, n_rows, V, H, arg);
