@@ -143,7 +143,7 @@ __device__ __forceinline__ float group_max_bits(float v) {
     return v;
 }
 
-template <int LPR, int NCH>
+template <int LPR, int NCH, bool FULL>     // FULL: the row has exactly LPR*NCH chunks (no chunk predicate)
 __global__ void __launch_bounds__(256) gate_frames_bf16_keyed(const bf16_t* __restrict__ logits, int64_t n_rows, int V,
                                                               float* __restrict__ H_out, int32_t* __restrict__ arg_out) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -161,19 +161,24 @@ __global__ void __launch_bounds__(256) gate_frames_bf16_keyed(const bf16_t* __re
     auto load_block = [&](int64_t blk, u32x4 (&c)[NCH]) {
         int64_t row = blk * ROWS_PER_BLOCK + threadIdx.x / LPR;
         if (row >= n_rows) row = n_rows - 1;
-        const u32x4* src = reinterpret_cast<const u32x4*>(logits + row * (int64_t)V);
+        const u32x4* src = reinterpret_cast<const u32x4*>(logits + row * (int64_t)V) + g;
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            const int idx = g + k * LPR;
-            if (idx < n_chunks) c[k] = __builtin_nontemporal_load(src + idx);
+            if (FULL || g + k * LPR < n_chunks) c[k] = __builtin_nontemporal_load(src + k * LPR);
             else c[k] = (u32x4){0xf14af14au, 0xf14af14au, 0xf14af14au, 0xf14af14au};   // about -1e30: finite, exp -> 0
         }
     };
 
-    u32x4 cur[NCH], nxt[NCH];
-    int64_t blk = blockIdx.x;
-    if (blk < n_blocks) load_block(blk, cur);
-    for (; blk < n_blocks; blk += gridDim.x) {
+    u32x4 buf0[NCH], buf1[NCH];
+    if ((int64_t)blockIdx.x < n_blocks) load_block(blockIdx.x, buf0);
+    // two row blocks per trip so that the register sets swap roles without copies
+    for (int64_t blk0 = blockIdx.x; blk0 < n_blocks; blk0 += 2 * (int64_t)gridDim.x) {
+      #pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int64_t blk = blk0 + half * (int64_t)gridDim.x;
+        if (blk >= n_blocks) break;
+        u32x4 (&cur)[NCH] = half ? buf1 : buf0;
+        u32x4 (&nxt)[NCH] = half ? buf0 : buf1;
         const int64_t nblk = blk + gridDim.x;
         if (nblk < n_blocks) load_block(nblk, nxt);
         const int64_t row = blk * ROWS_PER_BLOCK + threadIdx.x / LPR;
@@ -255,8 +260,7 @@ __global__ void __launch_bounds__(256) gate_frames_bf16_keyed(const bf16_t* __re
             H_out[row] = LN2 * (__builtin_amdgcn_logf(S) - W2 / S);
             arg_out[row] = arg;
         }
-#pragma unroll
-        for (int k = 0; k < NCH; ++k) cur[k] = nxt[k];
+      }
     }
 }
 
@@ -353,10 +357,15 @@ static void launch_vec(const T* logits, int64_t n_rows, int V, float* H, int32_t
         // persistent launch: enough workgroups to fill 256 CUs several times over, no more than there is work
         const unsigned pgrid = grid < 256u * 8u ? grid : 256u * 8u;
         const bf16_t* z = logits;
-        if (nch <= 1) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 1>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
-        else if (nch <= 2) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 2>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
-        else if (nch <= 4) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 4>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
-        else hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, 8>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg);
+        const bool full = n_chunks == nch * LPR;
+#define SSD_GATE_LAUNCH(NCH_)                                                                                          \
+        if (full) hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, NCH_, true>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg); \
+        else hipLaunchKernelGGL((gate_frames_bf16_keyed<LPR, NCH_, false>), dim3(pgrid), dim3(256), 0, st, z, n_rows, V, H, arg)
+        if (nch <= 1) { SSD_GATE_LAUNCH(1); }
+        else if (nch <= 2) { SSD_GATE_LAUNCH(2); }
+        else if (nch <= 4) { SSD_GATE_LAUNCH(4); }
+        else { SSD_GATE_LAUNCH(8); }
+#undef SSD_GATE_LAUNCH
         return;
     }
     if (nch <= 1) hipLaunchKernelGGL((gate_frames_vec<T, LPR, 1>), dim3(grid), dim3(256), 0, st, logits, n_rows, V, H, arg);
