@@ -136,12 +136,24 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, con
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, epi);
 }
 
-// Tile choice: 256x256 with eight wavefronts (wave tile 128x64) when there are enough rows to fill
-// such tiles; 128x128 with four wavefronts otherwise (N is a multiple of 256 for every GEMM here).
+// Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
+// of 256 for every GEMM here); the tile height is picked per launch so that the number of tiles
+// wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
+// With few rows (M <= 128) the 128-high tile is the only sensible one.
 template <class Epi>
 static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
-    if (M > 512) launch_gemm<256, 256, 2, 4>(A, W, M, N, K, epi, st);
-    else launch_gemm<128, 128, 2, 2>(A, W, M, N, K, epi, st);
+    const int heights[3] = {256, 192, 128};
+    const double eff[3] = {1.0, 0.97, 0.90};
+    int best = 0;
+    double best_cost = 1e30;
+    for (int c = 0; c < 3; ++c) {
+        const long tiles = (long)((M + heights[c] - 1) / heights[c]) * (N / 256);
+        const double cost = (double)((tiles + 255) / 256) * heights[c] / eff[c];
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = c; }
+    }
+    if (best == 0) launch_gemm<256, 256, 2, 4>(A, W, M, N, K, epi, st);
+    else if (best == 1) launch_gemm<192, 256, 2, 4>(A, W, M, N, K, epi, st);
+    else launch_gemm<128, 256, 2, 4>(A, W, M, N, K, epi, st);
 }
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
