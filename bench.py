@@ -25,6 +25,14 @@ from workloads import (WORKLOADS, make_ctc_batch, make_ctc_to_llm_map, make_mode
 PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense 16-bit matrix peak (bf16 and fp16)
 PEAK_HBM_GBS = 8000.0
 
+# Memory traffic of the dominant kernel per launch, from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a
+# plain 1 GiB device copy (`--copy-reference`): FETCH_SIZE reads 524300 for 1048576 KiB (factor 2.0),
+# WRITE_SIZE reads 1048576 (factor 1.0).  See profiles/pmc_traffic_gemm_gate_up_cfg3.md.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg3_1b_ragged64": (340791.9 * 2.0 + 82304.0 * 1.0) * 1024.0,
+}
+
 
 def layer_gemm_flops(m, M):
     """2 * M * (parameters of the projection matrices of one layer)."""
@@ -136,7 +144,16 @@ def main():
     ap.add_argument("--workload", default="cfg3_1b_ragged64", choices=list(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-tokens", type=int, default=3000)
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy five times (scale reference for --pmc counters)")
     args = ap.parse_args()
+    if args.copy_reference:
+        a = torch.full((1 << 30,), 3, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (utterance-sharded data parallelism needs no collectives and is "
               "not built); run with --gpus 1", file=sys.stderr)
@@ -204,7 +221,9 @@ def main():
         "mean_accepted_prefix_frac": float(np.mean(acc_len / np.maximum(np.diff(meta["cu_d"]), 1))),
         "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel<EpiSwiglu> (gate/up projection + SiLU*mul)",
                      "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_MFMA_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_MFMA_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "traffic_unit": "bytes per launch (L2<->fabric, incl. Infinity Cache hits)",
+                     "algorithmic_bytes": 2.0 * (M * m.d_model + 2 * m.d_ff * m.d_model + M * m.d_ff),
                      "avg_launch_ms": avg_ms, "launches_timed": dom_n, "flops_per_launch": gate_up_flops},
         "breakdown_ms_per_step": breakdown,
         "all_projection_gemms": {"tflops": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
