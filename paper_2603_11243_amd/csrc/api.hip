@@ -165,7 +165,7 @@ int attn_tile_rows(int dtype) { return dtype == SSD_BF16 ? 128 : 4; }
 
 struct VerifyPlan {
     size_t row_src, pos, vrow, tiles, meta_bytes;     // metadata block, uploaded in one copy
-    size_t x, a, qkv, attn, gu, h, total;             // activations
+    size_t x, a, qkv, attn, gu, h, partials, total;   // activations
 };
 VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t utts) {
     VerifyPlan p;
@@ -184,6 +184,8 @@ VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t ut
     p.attn = o; o = align_up(o + (size_t)(M * dq) * es);
     p.gu = o; if (c.dtype == SSD_F32) o = align_up(o + (size_t)(M * 2 * c.d_ff) * 4);
     p.h = o; o = align_up(o + (size_t)(M * c.d_ff) * es);
+    p.partials = o;
+    if (c.dtype == SSD_BF16 && M <= SKINNY_MAX_ROWS) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * M * d * 4);
     p.total = o;
     return p;
 }
@@ -487,29 +489,34 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
     const int Mi = (int)M, d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
 
     { ProfScope ps(ctx, SSD_PROF_OTHER); launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, st); }
+    float* partials = reinterpret_cast<float*>(ws + p.partials);
+    const int64_t split_stride = (int64_t)Mi * d;
+    int pending = 1;            // K splits of the last residual projection still to be added to x (1: none)
     for (int l = 0; l < m.n_layers; ++l) {
-        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, st); }
+        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
+        pending = 1;
         if (m.dtype == SSD_BF16) {
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_O); launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, Mi, d, dq, ctx->ds_o[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Mi, d, dq, ctx->ds_o[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
+            pending = 1;
             { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Mi, m.d_ff, d, ctx->ds_gu[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, Mi, d, m.d_ff, ctx->ds_down[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, partials, Mi, d, m.d_ff, ctx->ds_down[l], st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
             launch_rope_f32((float*)qkv, d_pos, ctx->rope_tab, Mi, m.n_q_heads + m.n_kv_heads, m.head_dim, dq + 2 * dkv, st);
             launch_attn_f32((const float*)qkv, (float*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, m.head_dim, st);
             launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Mi, d, dq, F32_ADD, st);
-            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, st);
             launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Mi, 2 * m.d_ff, d, F32_STORE, st);
             launch_swiglu_f32(gu, (float*)h, Mi, m.d_ff, st);
             launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Mi, d, m.d_ff, F32_ADD, st);
         }
     }
     // verification rows only: final RMSNorm of the positions that score a draft token
-    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, st); }
+    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, partials, pending, split_stride, st); }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }

@@ -53,25 +53,45 @@ void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, con
 // One wavefront per row; statistics in fp32.  d must be a multiple of 4.
 // T = bf16 gain with f16 output (MFMA operand type), or fp32 gain with fp32 output.
 template <typename T>
-__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+__global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                       const int32_t* __restrict__ row_idx, int n_rows, int d,
-                                                      float eps, T* __restrict__ out) {
+                                                      float eps, T* __restrict__ out, const float* __restrict__ partials,
+                                                      int n_splits, int64_t split_stride) {
     const int lane = threadIdx.x % 64;
     const int r = blockIdx.x * 4 + threadIdx.x / 64;
     if (r >= n_rows) return;
     const int64_t row = row_idx ? row_idx[r] : r;
-    const float4* src = reinterpret_cast<const float4*>(x + row * d);
+    float4* src = reinterpret_cast<float4*>(x + row * d);
     const int n4 = d / 4;
     float ss = 0.f;
-    for (int i = lane; i < n4; i += 64) {
-        const float4 v = src[i];
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    if (n_splits > 1) {
+        // pending K-split partial sums of the projection before this norm: add them in split order
+        for (int i = lane; i < n4; i += 64) {
+            float4 v = src[i];
+            for (int s = 0; s < n_splits; ++s) {
+                const float4 p = reinterpret_cast<const float4*>(partials + s * split_stride + row * d)[i];
+                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+            }
+            if (!row_idx) src[i] = v;
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    } else {
+        for (int i = lane; i < n4; i += 64) {
+            const float4 v = src[i];
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
     }
     ss = group_allreduce<64>(ss, OpSum());
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     T* dst = out + (int64_t)r * d;
     for (int i = lane; i < n4; i += 64) {
-        const float4 v = src[i];
+        float4 v = src[i];
+        if (n_splits > 1 && row_idx) {           // gathered rows are not written back: redo the sum
+            for (int s = 0; s < n_splits; ++s) {
+                const float4 p = reinterpret_cast<const float4*>(partials + s * split_stride + row * d)[i];
+                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+            }
+        }
         if constexpr (sizeof(T) == 2) {
             const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
             uint2 o;
@@ -85,14 +105,76 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
     }
 }
 
-void launch_rmsnorm(int dtype, const float* x, const void* gain, const int32_t* row_idx, int n_rows, int d, float eps,
-                    void* out, hipStream_t st) {
+// Same operation with one workgroup per row, for launches with few rows (there a wavefront per row
+// leaves most of the chip idle and serialises the split sums): every thread owns d/1024 float4s
+// and all its split loads are issued together.
+template <typename T, int MAXV>
+__global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x, const T* __restrict__ gain,
+                                                          const int32_t* __restrict__ row_idx, int d, float eps,
+                                                          T* __restrict__ out, const float* __restrict__ partials,
+                                                          int n_splits, int64_t split_stride) {
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    const int64_t row = row_idx ? row_idx[r] : r;
+    float4* src = reinterpret_cast<float4*>(x + row * d);
+    const int n4 = d / 4;
+    float4 v[MAXV];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+        const int i = threadIdx.x + k * 256;
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < n4) {
+            v[k] = src[i];
+            float4 p[SKINNY_MAX_SPLITS];
+#pragma unroll
+            for (int s = 0; s < SKINNY_MAX_SPLITS; ++s)
+                if (n_splits > 1 && s < n_splits) p[s] = reinterpret_cast<const float4*>(partials + s * split_stride + row * d)[i];
+#pragma unroll
+            for (int s = 0; s < SKINNY_MAX_SPLITS; ++s)
+                if (n_splits > 1 && s < n_splits) { v[k].x += p[s].x; v[k].y += p[s].y; v[k].z += p[s].z; v[k].w += p[s].w; }
+            if (n_splits > 1 && !row_idx) src[i] = v[k];
+            ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
+        }
+    }
+    ss = group_allreduce<64>(ss, OpSum());
+    if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = ss;
+    __syncthreads();
+    ss = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    T* dst = out + (int64_t)r * d;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+        const int i = threadIdx.x + k * 256;
+        if (i >= n4) continue;
+        if constexpr (sizeof(T) == 2) {
+            const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
+            uint2 o;
+            o.x = pack_f16x2(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x));
+            o.y = pack_f16x2(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y));
+            reinterpret_cast<uint2*>(dst)[i] = o;
+        } else {
+            const float4 g = reinterpret_cast<const float4*>(gain)[i];
+            reinterpret_cast<float4*>(dst)[i] = make_float4(v[k].x * inv * g.x, v[k].y * inv * g.y, v[k].z * inv * g.z, v[k].w * inv * g.w);
+        }
+    }
+}
+
+void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d, float eps,
+                    void* out, const float* partials, int n_splits, int64_t split_stride, hipStream_t st) {
     if (n_rows <= 0) return;
+    if (n_rows <= 512 && d <= 4096 && n_splits <= SKINNY_MAX_SPLITS) {
+        if (dtype == SSD_BF16)
+            hipLaunchKernelGGL((rmsnorm_row_kernel<bf16_t, 4>), dim3(n_rows), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, d, eps, (bf16_t*)out, partials, n_splits, split_stride);
+        else
+            hipLaunchKernelGGL((rmsnorm_row_kernel<float, 4>), dim3(n_rows), dim3(256), 0, st, x, (const float*)gain, row_idx, d, eps, (float*)out, partials, n_splits, split_stride);
+        return;
+    }
     const unsigned grid = (unsigned)((n_rows + 3) / 4);
     if (dtype == SSD_BF16)
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, n_rows, d, eps, (bf16_t*)out);
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, n_rows, d, eps, (bf16_t*)out, partials, n_splits, split_stride);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(grid), dim3(256), 0, st, x, (const float*)gain, row_idx, n_rows, d, eps, (float*)out);
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(grid), dim3(256), 0, st, x, (const float*)gain, row_idx, n_rows, d, eps, (float*)out, partials, n_splits, split_stride);
 }
 
 // ---------------------------------------------------------------------------------------------

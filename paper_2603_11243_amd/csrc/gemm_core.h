@@ -9,8 +9,10 @@
 //
 // A workgroup of WAVES_M x WAVES_N wavefronts computes a BM x BN tile.  K is consumed in slices of
 // BK = 64 (128 bytes per row) that go from global memory straight into LDS with
-// buffer_load_dwordx4 ... lds (no register staging), double-buffered: the loads of slice k+1 are in
-// flight while the MFMAs of slice k run, one barrier per slice.
+// buffer_load_dwordx4 ... lds (no register staging) through a ring of NSTAGE LDS stages: the loads
+// of the next NSTAGE-1 slices are in flight while the MFMAs of the current slice run, one barrier
+// per slice.  Big tiles use two stages (compute bound); the skinny tile for a handful of rows uses
+// more, because there the job is to keep enough weight bytes in flight.
 // LDS layout of a slice: row-major, 128 bytes per row, the eight 16-byte chunks of row r stored at
 // chunk position c ^ ((r >> 1) & 7).  A load instruction fills 1 KB of LDS with lane i's 16 bytes at
 // byte 16*i, so lane i fetches the global chunk that belongs at that position.  A fragment read
@@ -31,8 +33,8 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 constexpr int GEMM_BK = 64;
 constexpr int GEMM_ROW_BYTES = GEMM_BK * 2;
 
-template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * GEMM_ROW_BYTES; }
+template <int BM, int BN, int NSTAGE = 2>
+constexpr size_t gemm_lds_bytes() { return (size_t)NSTAGE * (BM + BN) * GEMM_ROW_BYTES; }
 
 __device__ __forceinline__ f16x8_t as_f16x8(const uint4& v) { return __builtin_bit_cast(f16x8_t, v); }
 
@@ -45,7 +47,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0xffffffff, 0x00020000);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE = 2>
 struct GemmTile {
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * WAVES;
@@ -58,9 +60,11 @@ struct GemmTile {
     static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile/thread mismatch");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
 
-    // acc must be zero-initialised by the caller.  smem: gemm_lds_bytes<BM,BN>() bytes, 16-byte aligned.
+    // acc must be zero-initialised by the caller.  smem: gemm_lds_bytes<BM,BN,NSTAGE>() bytes, 16-byte
+    // aligned.  Slices kt0 <= kt < kt1 of K are accumulated (K itself is the row stride of A and W).
     static __device__ __forceinline__ void run(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int K,
-                                               int m0, int n0, unsigned char* smem, f32x16_t (&acc)[TM][TN]) {
+                                               int m0, int n0, int kt0, int kt1, unsigned char* smem,
+                                               f32x16_t (&acc)[TM][TN]) {
         const int tid = threadIdx.x, lane = tid % 64;
         const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
         const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -119,35 +123,43 @@ struct GemmTile {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         };
 
-        // Software pipeline.  Invariant at the top of iteration kt: slice kt sits in stage kt&1 and
-        // its kk=0 fragments are in (a0, b0); the loads of slice kt+1 into the other stage are in
-        // flight.  The fragments of step kk+1 are read while the MFMAs of step kk run; the barrier
-        // that ends a slice sits between the last fragment read and the last MFMA block, so the
-        // first fragment read of the next slice and the global loads of the slice after it are
-        // issued before that MFMA block and overlap with it.
+        // Software pipeline over n = kt1 - kt0 slices; slice i lives in stage i % NSTAGE.
+        // Invariant at the top of iteration i: slice i has landed, its kk=0 fragments are in (a0, b0),
+        // slices i+1 .. i+NSTAGE-1 are in flight.  The fragments of step kk+1 are read while the
+        // MFMAs of step kk run; the barrier that ends a slice sits between the last fragment read
+        // and the last MFMA block, so the first fragment read of the next slice and the global
+        // loads that refill the freed stage are issued before that MFMA block and overlap with it.
         constexpr int KK = GEMM_BK / 16;
         static_assert(KK == 4, "pipeline below is written for four k-steps per slice");
-        const int KT = K / GEMM_BK;
+        static_assert(NSTAGE >= 2 && (NSTAGE - 2) * (A_LOADS + B_LOADS) <= 63, "vmcnt range");
+        // s_waitcnt immediates: lgkmcnt(0) with vmcnt(V): V low 4 bits in [3:0], high 2 bits in [15:14]
+        constexpr int V_KEEP = (NSTAGE - 2) * (A_LOADS + B_LOADS);     // loads of the younger slices may stay out
+        constexpr int WAIT_KEEP = 0x0070 | (V_KEEP & 15) | ((V_KEEP >> 4) << 14);
+        constexpr int WAIT_KEEP_NO_LGKM = WAIT_KEEP | 0x0F00;
+        const int n = kt1 - kt0;
         f16x8_t a0[TM], b0[TN], a1[TM], b1[TN];
-        issue_loads(0, 0);
-        if (KT > 1) issue_loads(1, 1);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+        for (int s = 0; s < NSTAGE; ++s)
+            if (s < n) issue_loads(kt0 + s, s);
+        if (n >= NSTAGE) __builtin_amdgcn_s_waitcnt(WAIT_KEEP_NO_LGKM); else __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         read_frags(0, 0, a0, b0);
-        for (int kt = 0; kt < KT; ++kt) {
-            const int stage = kt & 1;
+        int stage = 0;
+        for (int i = 0; i < n; ++i) {
             read_frags(stage, 1, a1, b1);
             mfma_block(a0, b0);
             read_frags(stage, 2, a0, b0);
             mfma_block(a1, b1);
             read_frags(stage, 3, a1, b1);
             mfma_block(a0, b0);
-            // all reads of `stage` are issued; wait for them and for slice kt+1 (loaded during this slice)
-            __builtin_amdgcn_s_waitcnt(0x0070);    // vmcnt(0) lgkmcnt(0)
+            // all reads of `stage` are issued; wait for them and for slice i+1 (its loads are the oldest)
+            if (i + NSTAGE < n + 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP); else __builtin_amdgcn_s_waitcnt(0x0070);
             __syncthreads();
-            if (kt + 2 < KT) issue_loads(kt + 2, stage);
-            if (kt + 1 < KT) read_frags(stage ^ 1, 0, a0, b0);
+            if (i + NSTAGE < n) issue_loads(kt0 + i + NSTAGE, stage);
+            const int next = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+            if (i + 1 < n) read_frags(next, 0, a0, b0);
             mfma_block(a1, b1);
+            stage = next;
         }
     }
 };

@@ -6,6 +6,8 @@
 // weight tensor was scaled by when it was converted to f16.
 // The fused weight layouts are produced by pack_qkv_kernel / pack_gate_up_kernel: a column and the
 // column it must be combined with sit in neighbouring 32-wide accumulator blocks of the same lane.
+#include <type_traits>
+
 #include "gemm_core.h"
 #include "ssd_internal.h"
 
@@ -101,14 +103,37 @@ struct EpiSwiglu {
     }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+// Stores the scaled accumulator as an fp32 partial sum of one K split: part[split][row][col].
+// Whoever consumes it (the RMSNorm that follows) adds the splits in a fixed order.
+struct EpiPartial {
+    float* part; int ld; int64_t split_stride; float descale;
+    template <int TM, int TN>
+    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
+        float* base = part + split * split_stride;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + acc_row(i, r, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) base[(int64_t)row * ld + col0 + acc_col(j, lane)] = acc[i][j][r] * descale;
+            }
+    }
+};
+
+// grid = tiles * splits; split s of a tile accumulates K slices [s*KT/splits, (s+1)*KT/splits)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
-gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
-    using Tile = GemmTile<BM, BN, WAVES_M, WAVES_N>;
+gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, int splits, Epi epi) {
+    using Tile = GemmTile<BM, BN, WAVES_M, WAVES_N, NSTAGE>;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    const int split = blockIdx.x % splits;
     int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    tile_of_workgroup(blockIdx.x / splits, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    const int KT = K / GEMM_BK;
+    const int kt0 = (int)((int64_t)KT * split / splits), kt1 = (int)((int64_t)KT * (split + 1) / splits);
     f32x16_t acc[Tile::TM][Tile::TN];
 #pragma unroll
     for (int i = 0; i < Tile::TM; ++i)
@@ -116,32 +141,37 @@ gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M
         for (int j = 0; j < Tile::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile::run(A, W, M, K, tm * BM, tn * BN, smem_raw, acc);
+    Tile::run(A, W, M, K, tm * BM, tn * BN, kt0, kt1, smem_raw, acc);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
+    if constexpr (std::is_same<Epi, EpiPartial>::value)
+        epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane, split);
+    else
+        epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
-static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, class Epi>
+static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
     if (M <= 0) return;
-    auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, Epi>;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, Epi>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, NSTAGE>();
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
     const int tiles = ((M + BM - 1) / BM) * (N / BN);
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, epi);
+    hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, splits, epi);
 }
 
 // Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
 // of 256 for every GEMM here); the tile height is picked per launch so that the number of tiles
 // wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
-// With few rows (M <= 128) the 128-high tile is the only sensible one.
+// With at most 128 rows the job is weight streaming: a skinny 128 x 64 tile (four wavefronts, each
+// 32 rows x 64 columns) with a four-stage LDS ring gives N/64 workgroups with 72 KB in flight each.
 template <class Epi>
 static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= SKINNY_MAX_ROWS) { launch_gemm<128, 64, 4, 1, 4>(A, W, M, N, K, 1, epi, st); return; }
     const int heights[3] = {256, 192, 128};
     const double eff[3] = {1.0, 0.97, 0.90};
     int best = 0;
@@ -151,9 +181,9 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K,
         const double cost = (double)((tiles + 255) / 256) * heights[c] / eff[c];
         if (cost < best_cost - 1e-9) { best_cost = cost; best = c; }
     }
-    if (best == 0) launch_gemm<256, 256, 2, 4>(A, W, M, N, K, epi, st);
-    else if (best == 1) launch_gemm<192, 256, 2, 4>(A, W, M, N, K, epi, st);
-    else launch_gemm<128, 256, 2, 4>(A, W, M, N, K, epi, st);
+    if (best == 0) launch_gemm<256, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
+    else if (best == 1) launch_gemm<192, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
+    else launch_gemm<128, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
 }
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
@@ -163,9 +193,28 @@ void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16
     launch_by_shape(A, Wqkv_packed, M, N, d_model, epi, st);
 }
 
-void launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, int M, int N, int K, float descale, hipStream_t st) {
+int gemm_residual_splits(int M, int N, int K) {
+    if (M > SKINNY_MAX_ROWS) return 1;
+    int splits = 1;
+    while (splits < SKINNY_MAX_SPLITS && (N / 64) * splits < 256 && K / GEMM_BK / (splits * 2) >= 4) splits *= 2;
+    return splits;
+}
+
+// x += A W^T.  With few rows the K range is split over several workgroups per tile to get enough
+// of them for weight streaming; the splits land in `partials` ([splits][M][N] fp32) and the caller
+// hands them to the next RMSNorm, which adds them to x in a fixed order.  Returns the split count
+// (1: x has been updated in place).
+int launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, float* partials, int M, int N, int K,
+                         float descale, hipStream_t st) {
+    const int splits = gemm_residual_splits(M, N, K);
+    if (splits > 1) {
+        EpiPartial epi{partials, N, (int64_t)M * N, descale};
+        launch_gemm<128, 64, 4, 1, 4>(A, W, M, N, K, splits, epi, st);
+        return splits;
+    }
     EpiResidual epi{x, N, descale};
     launch_by_shape(A, W, M, N, K, epi, st);
+    return 1;
 }
 
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,

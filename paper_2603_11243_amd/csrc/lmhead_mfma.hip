@@ -11,8 +11,7 @@
 
 namespace ssd {
 
-constexpr int LM_BM = 256, LM_BN = 256, LM_WM = 2, LM_WN = 4;
-constexpr int LM_WTN = LM_BN / LM_WN;          // columns per group
+constexpr int LM_WTN = 64;          // columns per group: every tile variant below has a 64-column wave tile
 
 int lmhead_col_groups(int vocab) { return vocab / LM_WTN; }
 
@@ -27,12 +26,13 @@ __device__ __forceinline__ float row_allreduce32(float v, Op op) {
     return v;
 }
 
-template <bool GREEDY>
+template <int LM_BM, int LM_BN, int LM_WM, int LM_WN, int LM_NS, bool GREEDY>
 __global__ void __launch_bounds__(64 * LM_WM * LM_WN)
 lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,
                    int Mv, int d, int vocab, float2* __restrict__ part_ms, float* __restrict__ tgt_logit,
                    int2* __restrict__ part_arg, float descale) {
-    using Tile = GemmTile<LM_BM, LM_BN, LM_WM, LM_WN>;
+    using Tile = GemmTile<LM_BM, LM_BN, LM_WM, LM_WN, LM_NS>;
+    static_assert(Tile::WTN == LM_WTN, "column groups are 64 wide");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (Mv + LM_BM - 1) / LM_BM;
     // row tiles vary fastest: workgroups that run together share one slab of W_lm
@@ -44,7 +44,7 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
         for (int j = 0; j < Tile::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile::run(hv, w_lm, Mv, d, tm * LM_BM, tn * LM_BN, smem_raw, acc);
+    Tile::run(hv, w_lm, Mv, d, tm * LM_BM, tn * LM_BN, 0, d / GEMM_BK, smem_raw, acc);
 
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / LM_WN, wn = wave % LM_WN;
@@ -98,17 +98,14 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
         }
 }
 
-template __global__ void lmhead_mfma_kernel<true>(const f16_t*, const f16_t*, const int32_t*, int, int, int, float2*, float*, int2*, float);
-template __global__ void lmhead_mfma_kernel<false>(const f16_t*, const f16_t*, const int32_t*, int, int, int, float2*, float*, int2*, float);
-
-void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
-                        float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
-                        hipStream_t st) {
-    if (Mv <= 0) return;
-    constexpr size_t lds = gemm_lds_bytes<LM_BM, LM_BN>();
-    const int tiles = ((Mv + LM_BM - 1) / LM_BM) * (vocab / LM_BN);
-    auto kern_greedy = lmhead_mfma_kernel<true>;
-    auto kern_plain = lmhead_mfma_kernel<false>;
+template <int BM, int BN, int WM, int WN, int NS>
+static void launch_lmhead_cfg(const f16_t* hv, const f16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+                              float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
+                              hipStream_t st) {
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, NS>();
+    const int tiles = ((Mv + BM - 1) / BM) * (vocab / BN);
+    auto kern_greedy = lmhead_mfma_kernel<BM, BN, WM, WN, NS, true>;
+    auto kern_plain = lmhead_mfma_kernel<BM, BN, WM, WN, NS, false>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_greedy), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -116,11 +113,20 @@ void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t*
         attr_set = true;
     }
     if (want_greedy)
-        hipLaunchKernelGGL(kern_greedy, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
-                           Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
+        hipLaunchKernelGGL(kern_greedy, dim3(tiles), dim3(64 * WM * WN), lds, st, hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
     else
-        hipLaunchKernelGGL(kern_plain, dim3(tiles), dim3(64 * LM_WM * LM_WN), lds, st, hv, w_lm, targets,
-                           Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
+        hipLaunchKernelGGL(kern_plain, dim3(tiles), dim3(64 * WM * WN), lds, st, hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, descale);
+}
+
+// Tile by row count: up to 32 rows the whole job is streaming W_lm once (32 x 256 tile, four-stage
+// ring); up to 128 rows a 128 x 64 tile; otherwise the compute-bound 256 x 256 tile.
+void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+                        float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
+                        hipStream_t st) {
+    if (Mv <= 0) return;
+    if (Mv <= 32) launch_lmhead_cfg<32, 256, 1, 4, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    else if (Mv <= 128) launch_lmhead_cfg<128, 64, 4, 1, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    else launch_lmhead_cfg<256, 256, 2, 4, 2>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
 }
 
 // One wavefront per row merges the per-group partials.

@@ -34,9 +34,11 @@ struct AttnTile {
 void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
                        const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
                        hipStream_t st);
-// a = rmsnorm(x) * gain;  rows optionally gathered through row_idx (NULL = identity)
-void launch_rmsnorm(int dtype, const float* x, const void* gain, const int32_t* row_idx, int n_rows, int d,
-                    float eps, void* out, hipStream_t st);
+// a = rmsnorm(x) * gain;  rows optionally gathered through row_idx (NULL = identity).
+// If n_splits > 1, x[row] is first increased by partials[s][row] for s = 0..n_splits-1 (fixed order;
+// partials is [n_splits][M][d] fp32) and, when row_idx is NULL, written back.
+void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d,
+                    float eps, void* out, const float* partials, int n_splits, int64_t split_stride, hipStream_t st);
 
 // ---- f32_path.hip (all-fp32 decoder for the tiny configuration)
 enum F32Epilogue { F32_STORE = 0, F32_ADD = 1 };
@@ -54,8 +56,12 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
                           hipStream_t st);
-void launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, int M, int N, int K, float descale,
-                          hipStream_t st);
+constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
+constexpr int SKINNY_MAX_SPLITS = 8;
+int gemm_residual_splits(int M, int N, int K);
+// returns the number of K splits written to `partials` ([splits][M][N] fp32), or 1 if x was updated in place
+int launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, float* partials, int M, int N, int K,
+                         float descale, hipStream_t st);
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
                         float descale, hipStream_t st);
 void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,

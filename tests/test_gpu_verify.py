@@ -148,7 +148,9 @@ def test_tiny_f32_causality_and_batch_isolation():
 # ------------------------------------------------------------------ bf16, reduced depth, whole batch
 
 @pytest.mark.parametrize("name,layers,B", [("cfg3_1b_ragged64", 2, 12), ("cfg5_3b_ragged128", 1, 10),
-                                           ("cfg4_1b_long_ml", 1, 2)])
+                                           ("cfg4_1b_long_ml", 1, 2),
+                                           ("cfg2_1b_b1", 3, 1),          # <= 128 rows: skinny tiles, split-K partials
+                                           ("cfg3_1b_ragged64", 1, 2)])   # 33..128 verification rows
 def test_bf16_reduced_depth_whole_batch(name, layers, B):
     wl = scaled_down(WORKLOADS[name], n_layers=layers, B=B)
     wl = replace(wl, gate_rate=0.0)
