@@ -58,16 +58,29 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict_
     const float sc = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(128)
 
     const int kv_end = min(t.seq_len, t.q_start + 128);             // keys needed by this tile
+    // K/V blocks go global -> registers -> LDS; the registers of block kb+1 are loaded while block kb
+    // is being multiplied.  K: thread owns (key = c/16, 8 dims) -> coalesced rows.  V: thread owns
+    // (key = tid%64, 8 dims) so that a wavefront writes 64 neighbouring keys of one V^T row.
+    uint4 k_reg[4], v_reg[4];
+    auto load_kv = [&](int kb) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = tid + it * 256;
+            const int krow = min(kb + c / 16, t.seq_len - 1);
+            k_reg[it] = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + (c % 16) * 8);
+            const int vrow = min(kb + tid % 64, t.seq_len - 1);
+            v_reg[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)vrow * ldq + (tid / 64 + 4 * it) * 8);
+        }
+    };
+    load_kv(0);
     for (int kb = 0; kb < kv_end; kb += ATT_KB) {
         // ---- stage K (row-major) and V (transposed, permuted) blocks
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int c = tid + it * 256;
-            const int key = c / 16, dc = c % 16;
-            const int krow = min(kb + key, t.seq_len - 1);
-            const uint4 kv = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + dc * 8);
-            *reinterpret_cast<uint4*>(Ks + key * ATT_K_STRIDE + dc * 8) = kv;
-            const uint4 vv = *reinterpret_cast<const uint4*>(vbase + (int64_t)krow * ldq + dc * 8);
+            *reinterpret_cast<uint4*>(Ks + (c / 16) * ATT_K_STRIDE + (c % 16) * 8) = k_reg[it];
+            const int key = tid % 64, dc = tid / 64 + 4 * it;
+            const uint4 vv = v_reg[it];
             const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
             f16_t* vd = Vt + (dc * 8) * ATT_V_STRIDE + slot;
             vd[0 * ATT_V_STRIDE] = (f16_t)(vv.x & 0xffff); vd[1 * ATT_V_STRIDE] = (f16_t)(vv.x >> 16);
@@ -75,6 +88,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict_
             vd[4 * ATT_V_STRIDE] = (f16_t)(vv.z & 0xffff); vd[5 * ATT_V_STRIDE] = (f16_t)(vv.z >> 16);
             vd[6 * ATT_V_STRIDE] = (f16_t)(vv.w & 0xffff); vd[7 * ATT_V_STRIDE] = (f16_t)(vv.w >> 16);
         }
+        if (kb + ATT_KB < kv_end) load_kv(kb + ATT_KB);
         __syncthreads();
         if (wave_live && kb <= q_first + 31) {
             // ---- S^T for the two 32-key halves of the block
