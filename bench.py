@@ -136,6 +136,32 @@ def cpu_baseline(wl, step, weights, meta, budget_tokens):
             "utterances_per_s": len(pick) / dt}
 
 
+def gate_roofline(ctx, wl, device):
+    """Bandwidth of ctc_gate on a working set far larger than the 256 MB Infinity Cache: the workload's
+    frame shape (V_ctc, storage type) repeated to about 1.6 GB, 400-frame utterances, HIP events."""
+    V = wl.V_ctc
+    dt = torch.bfloat16 if wl.model.dtype == "bf16" else torch.float32
+    T = 400
+    n_utts = max(1, int(1.6e9 / (V * (2 if dt == torch.bfloat16 else 4))) // T)
+    n_rows = n_utts * T
+    cu = np.arange(n_utts + 1, dtype=np.int32) * T
+    z = torch.randn(n_rows, V, device=device, dtype=torch.float32).to(dt)
+    z[:, 7] += 6.0
+    ctx.reserve(max_frames=n_rows, max_utts=n_utts)
+    out = ctx.ctc_gate(z, cu, wl.blank_id, wl.tau_ctc)
+    torch.cuda.synchronize()
+    ctx.profile_select("gate")
+    for _ in range(10):
+        ctx.ctc_gate(z, cu, wl.blank_id, wl.tau_ctc, out=out)
+    ms, n = ctx.profile_read()["gate"]
+    ctx.profile_select(-2)
+    nbytes = z.numel() * z.element_size() + n_rows * 12          # scores in; entropy, argmax, draft slot out
+    gbs = nbytes / (ms / n * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "ctc_gate (frames kernel + per-utterance kernel)", "achieved": gbs,
+            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "avg_call_ms": ms / n,
+            "frames": n_rows, "V_ctc": V, "storage": str(dt).replace("torch.", ""), "bytes_per_frame": V * z.element_size() + 12}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +255,11 @@ def main():
         "all_projection_gemms": {"tflops": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
                                  "frac_of_peak": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
     }
+    tf, ghz = ctx.measure_mfma_ceiling(20000)
+    out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
+                                       "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
+    out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
+    out["gate_roofline"] = gate_roofline(ctx, wl, device)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)
     print(json.dumps(out))

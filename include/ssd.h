@@ -114,6 +114,12 @@ enum ssd_prof_class {
     SSD_PROF_N_CLASSES = 8
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
+/* Measurement aid: runs `iters` rounds of 8 independent v_mfma_f32_32x32x16_f16 per wavefront on
+ * pseudo-random register operands, four wavefronts on every CU, no memory traffic, and reports the
+ * sustained rate (TFLOP/s) and the shader clock observed meanwhile (GHz): the ceiling that power
+ * and clock management leave for the matrix cores on this device.  Uses the first 256 KB of the
+ * workspace and waits for the stream. */
+int ssd_measure_mfma_ceiling(ssd_ctx *ctx, int iters, float *tflops /*host*/, float *shader_ghz /*host*/);
 int ssd_profile_read(ssd_ctx *ctx, float *total_ms /*host [8]*/, int32_t *launches /*host [8]*/);
 
 /* Sec. 2.1.  For every frame t of every utterance: softmax over the V_ctc scores (blank included),

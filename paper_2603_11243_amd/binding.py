@@ -18,7 +18,7 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
            -5: "SSD_EUNSUPPORTED"}
 
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
-           "ssd_profile_select", "ssd_profile_read", "ctc_gate", "verify_forward", "accept_prefix"]
+           "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other"]
@@ -64,6 +64,8 @@ def load_library() -> C.CDLL:
     lib.ssd_profile_select.restype = i32
     lib.ssd_profile_read.argtypes = [vp, vp, vp]
     lib.ssd_profile_read.restype = i32
+    lib.ssd_measure_mfma_ceiling.argtypes = [vp, i32, vp, vp]
+    lib.ssd_measure_mfma_ceiling.restype = i32
     lib.ctc_gate.argtypes = [vp, vp, i32, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.ctc_gate.restype = i32
     lib.verify_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
@@ -176,6 +178,11 @@ class Context:
         n = np.zeros(len(PROF_CLASSES), dtype=np.int32)
         self._check(self._lib.ssd_profile_read(self._h, ms.ctypes.data, n.ctypes.data))
         return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(PROF_CLASSES)}
+
+    def measure_mfma_ceiling(self, iters: int = 20000):
+        t, g = C.c_float(), C.c_float()
+        self._check(self._lib.ssd_measure_mfma_ceiling(self._h, iters, C.byref(t), C.byref(g)))
+        return float(t.value), float(g.value)
 
     # ---- the three calls -------------------------------------------------------------------
 

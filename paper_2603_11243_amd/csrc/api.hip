@@ -398,6 +398,33 @@ int ssd_profile_read(ssd_ctx* ctx, float* total_ms, int32_t* launches) {
     return SSD_OK;
 }
 
+int ssd_measure_mfma_ceiling(ssd_ctx* ctx, int iters, float* tflops, float* shader_ghz) {
+    if (!ctx || !tflops || !shader_ghz || iters <= 0) return SSD_EINVAL;
+    const int n_wg = 256;                                  // one workgroup of four wavefronts per CU
+    const size_t need = (size_t)n_wg * 256 * 4 + 256;
+    if (!ctx->ws || ctx->ws_bytes < need) return fail(ctx, SSD_EWORKSPACE, "ssd_measure_mfma_ceiling: workspace of %zu bytes needed", need);
+    float* sink = static_cast<float*>(ctx->ws);
+    long long* clocks = reinterpret_cast<long long*>(static_cast<char*>(ctx->ws) + (size_t)n_wg * 256 * 4);
+    hipEvent_t e0, e1;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    HIP_TRY(ctx, hipEventCreate(&e1));
+    launch_mfma_ceiling(sink, clocks, n_wg, std::max(1, iters / 20), ctx->stream);       // warm-up
+    HIP_TRY(ctx, hipEventRecord(e0, ctx->stream));
+    launch_mfma_ceiling(sink, clocks, n_wg, iters, ctx->stream);
+    HIP_TRY(ctx, hipEventRecord(e1, ctx->stream));
+    HIP_TRY(ctx, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, e0, e1));
+    long long hc[2] = {0, 1};
+    HIP_TRY(ctx, hipMemcpy(hc, clocks, sizeof hc, hipMemcpyDeviceToHost));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    const double flops = (double)n_wg * 4 * (double)iters * 8 * 32768.0;      // 32x32x16 MFMA = 32768 flop
+    *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+    *shader_ghz = (float)((double)hc[0] / ((double)hc[1] * 10.0));            // constant clock ticks at 100 MHz
+    return SSD_OK;
+}
+
 int ctc_gate(ssd_ctx* ctx, const void* logits, int dtype, const int32_t* cu_frames, int B, int V_ctc, int blank_id,
              float tau_ctc, float* frame_entropy, int32_t* frame_argmax, float* max_entropy, uint8_t* gate_pass,
              int32_t* draft_ctc, int32_t* draft_len) {

@@ -83,6 +83,9 @@ void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, 
 void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
                          hipStream_t st);
 
+// measurement aid: MFMA-only loop (sink: n_workgroups*256 floats, clocks: 2 x int64)
+void launch_mfma_ceiling(float* sink, long long* clocks, int n_workgroups, int iters, hipStream_t st);
+
 // ---- accept (shared by both dtypes): first failing token per utterance
 void launch_accept_scan(const float* logp, const int32_t* cu_draft_dev, int Bv, float ln_tau, int32_t* accept_len,
                         uint8_t* all_accepted, hipStream_t st);
