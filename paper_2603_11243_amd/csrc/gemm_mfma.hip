@@ -29,22 +29,30 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_
     tn = in / rows;
 }
 
+// The epilogues below read first and write afterwards, block by block: a load placed after a store
+// through an unrelated pointer cannot be moved ahead of it by the compiler, and a read-modify-write
+// written element by element degenerates into one exposed memory round trip per element.
 struct EpiResidual {
     float* x; int ldx; float descale;
     template <int TM, int TN>
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            float old[16][TN];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = min(row0 + acc_row(i, r, lane), M - 1);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) old[r][j] = x[(int64_t)row * ldx + col0 + acc_col(j, lane)];
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = row0 + acc_row(i, r, lane);
                 if (row >= M) continue;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    float* p = x + (int64_t)row * ldx + col0 + acc_col(j, lane);
-                    *p += acc[i][j][r] * descale;
-                }
+                for (int j = 0; j < TN; ++j) x[(int64_t)row * ldx + col0 + acc_col(j, lane)] = old[r][j] + acc[i][j][r] * descale;
             }
+        }
     }
 };
 
@@ -55,29 +63,31 @@ struct EpiQkvRope {
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert(TN % 2 == 0, "rotation partners live in block pairs");
 #pragma unroll
-        for (int j = 0; j < TN; j += 2) {
-            const int p = col0 + j * 32;                    // packed column of this block pair (multiple of 64)
-            const bool rot = p < d_rot;
-            const int head = p / 128, grp = (p % 128) / 64;
-            const int i_rot = grp * 32 + lane % 32;
-            const int c0 = rot ? head * 128 + i_rot : p + lane % 32;
-            const int c1 = rot ? c0 + 64 : c0 + 32;
+        for (int i = 0; i < TM; ++i) {
+            int p_row[16];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int r = 0; r < 16; ++r) p_row[r] = pos[min(row0 + acc_row(i, r, lane), M - 1)];
+#pragma unroll
+            for (int j = 0; j < TN; j += 2) {
+                const int p = col0 + j * 32;                    // packed column of this block pair (multiple of 64)
+                const bool rot = p < d_rot;
+                const int head = p / 128, grp = (p % 128) / 64;
+                const int i_rot = grp * 32 + lane % 32;
+                const int c0 = rot ? head * 128 + i_rot : p + lane % 32;
+                const int c1 = rot ? c0 + 64 : c0 + 32;
+                float2 cs[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cs[r] = rot ? rope_tab[(int64_t)p_row[r] * 64 + i_rot] : make_float2(1.f, 0.f);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = row0 + acc_row(i, r, lane);
                     if (row >= M) continue;
-                    float a = acc[i][j][r] * descale, b = acc[i][j + 1][r] * descale;
-                    if (rot) {
-                        const float2 cs = rope_tab[(int64_t)pos[row] * 64 + i_rot];
-                        const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
-                        a = ra; b = rb;
-                    }
+                    const float a = acc[i][j][r] * descale, b = acc[i][j + 1][r] * descale;
                     f16_t* o = qkv + (int64_t)row * ldq;
-                    o[c0] = f32_to_f16(a);
-                    o[c1] = f32_to_f16(b);
+                    o[c0] = f32_to_f16(a * cs[r].x - b * cs[r].y);
+                    o[c1] = f32_to_f16(b * cs[r].x + a * cs[r].y);
                 }
+            }
         }
     }
 };
