@@ -234,6 +234,32 @@ def draft_logp(weights: Dict, cfg, speech_emb, cu_speech, prompt_ids, cu_prompt,
     return tuple(res)
 
 
+def ar_fallback(weights: Dict, cfg, speech_emb_b, prompt_ids_b, prefix_ids_b, n_steps: int) -> np.ndarray:
+    """Greedy auto-regressive continuation from an accepted prefix (Sec. 2.3, Eq. 6, for one utterance).
+
+    The sequence [speech; prompt; prefix] is extended one token at a time; every token is the
+    lowest-index argmax of the next-token distribution at the last position.  Plain and quadratic:
+    the whole forward is recomputed for every token (no cache).  Returns n_steps + 1 tokens: the
+    first is the model's own choice right after the prefix (the token that replaces the first
+    rejected draft token), the rest continue from it.
+    """
+    w_f, w_lm = _f64(weights["norm_final"]), _f64(weights["lm_head"])
+    sp = _f64(speech_emb_b)
+    ids = [int(t) for t in list(prompt_ids_b) + list(prefix_ids_b)]
+    if len(sp) + len(ids) < 1:
+        raise ValueError("nothing to condition on")
+    out = []
+    for _ in range(n_steps + 1):
+        idx = np.asarray(ids, dtype=np.int64)
+        rows = [sp] + ([_f64(weights["embed"][idx])] if len(idx) else [])
+        x = decoder_hidden([np.concatenate(rows, axis=0)], weights, cfg)[0]
+        h = rmsnorm(x[-1], w_f, cfg.rms_eps)
+        tok = int(np.argmax(w_lm @ h))
+        out.append(tok)
+        ids.append(tok)
+    return np.asarray(out, dtype=np.int32)
+
+
 # ------------------------------------------------------------------------ accept
 
 def accept_prefix(logp: Sequence[float], tau_slm: float) -> Dict:

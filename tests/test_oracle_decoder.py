@@ -200,6 +200,30 @@ def test_lm_head_normalisation_and_gather():
         assert abs(lp2[0][i] - want) < 1e-12
 
 
+def test_ar_fallback_is_consistent_with_teacher_forced_scoring():
+    """Feeding the generated tokens back as a draft: the greedy token at every scoring position is the
+    token that was generated there (ties aside, none here), and the first token is the greedy choice
+    after the prefix.  This ties the AR loop to the scoring function pinned above."""
+    cfg = SMALL
+    w = _weights(cfg)
+    inp = _inputs(cfg, S=[5], P=[3], U=[4], seed=11)
+    toks = O.ar_fallback(w, cfg, inp["speech_emb"], inp["prompt_ids"], inp["draft_ids"][:2], n_steps=5)
+    assert len(toks) == 6
+    draft = np.concatenate([inp["draft_ids"][:2], toks]).astype(np.int32)
+    _, greedy = O.draft_logp(w, cfg, inp["speech_emb"], inp["cu_speech"], inp["prompt_ids"], inp["cu_prompt"], draft,
+                             np.array([0, len(draft)], np.int32), return_greedy=True)
+    # row i (0-based) scores draft token i: rows 2.. score the generated tokens
+    assert list(greedy[0][2:]) == list(toks)
+    # an empty prefix and zero steps
+    t0 = O.ar_fallback(w, cfg, inp["speech_emb"], inp["prompt_ids"], [], n_steps=0)
+    _, g0 = O.draft_logp(w, cfg, inp["speech_emb"], inp["cu_speech"], inp["prompt_ids"], inp["cu_prompt"],
+                         np.array([1], np.int32), np.array([0, 1], np.int32), return_greedy=True)
+    assert t0[0] == g0[0][0]
+    # the continuation does not depend on what the rejected draft tokens were: only the prefix matters
+    toks2 = O.ar_fallback(w, cfg, inp["speech_emb"], inp["prompt_ids"], inp["draft_ids"][:2], n_steps=5)
+    assert np.array_equal(toks, toks2)
+
+
 def test_accept_prefix_hand_cases_with_paper_thresholds():
     ln = math.log
     for tau in (GOLD["tau_slm_high_rtfx"], GOLD["tau_slm_high_accuracy"]):
