@@ -162,6 +162,42 @@ def gate_roofline(ctx, wl, device):
             "frames": n_rows, "V_ctc": V, "storage": str(dt).replace("torch.", ""), "bytes_per_frame": V * z.element_size() + 12}
 
 
+def ar_fallback_leg(ctx, wl, meta, tau, n_steps=16):
+    """Eq. 6 after the timed path: verify with the K/V cache, accept with greedy tokens, then n_steps of
+    greedy continuation for the utterances whose draft was not fully accepted.  A decode step streams
+    every layer's weights and the LM head once, so it is graded against HBM bandwidth."""
+    m = wl.model
+    S, P, U = np.diff(meta["cu_s"]), np.diff(meta["cu_p"]), np.diff(meta["cu_d"])
+    cap = S + P + U + n_steps + 1
+    kv_start = np.concatenate([[0], np.cumsum(cap)[:-1]]).astype(np.int32)
+    ctx.set_kv_cache(int(cap.sum()))
+    ctx.reserve(ar_utts=len(U), ar_steps=n_steps)
+    hv = ctx.verify_forward(meta["speech"], meta["cu_s"], meta["prompt"], meta["cu_p"], meta["draft_ids"], meta["cu_d"],
+                            kv_start=kv_start)
+    acc = ctx.accept_prefix(hv, meta["draft_ids"], meta["cu_d"], tau, want_greedy=True)
+    acc_len = acc["accept_len"].cpu().numpy()
+    rej = np.flatnonzero(acc_len < U)
+    if len(rej) == 0:
+        return None
+    idx = torch.from_numpy((meta["cu_d"][:-1][rej] + acc_len[rej]).astype(np.int64)).to(hv.device)
+    first = acc["greedy_tok"][idx].contiguous()
+    ctx_len = (S + P + acc_len)[rej].astype(np.int32)
+    out = ctx.ar_fallback(kv_start[rej], ctx_len, first, n_steps)           # warm-up
+    torch.cuda.synchronize()
+    ctx.profile_select("ar_fallback")
+    for _ in range(3):
+        ctx.ar_fallback(kv_start[rej], ctx_len, first, n_steps, out=out)
+    ms, n = ctx.profile_read()["ar_fallback"]
+    ctx.profile_select(-2)
+    step_ms = ms / n / n_steps
+    weight_bytes = 2.0 * (m.n_layers * m.params_per_layer() + m.vocab * m.d_model)
+    gbs = weight_bytes / (step_ms * 1e-3) / 1e9
+    return {"rejected_utterances": int(len(rej)), "steps": n_steps, "ms_per_step": step_ms,
+            "tokens_per_s": len(rej) / (step_ms * 1e-3),
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                         "algorithmic_bytes_per_step": weight_bytes}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -259,6 +295,7 @@ def main():
     out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
                                        "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
     out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
+    out["ar_fallback"] = ar_fallback_leg(ctx, wl, meta, tau)
     out["gate_roofline"] = gate_roofline(ctx, wl, device)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)

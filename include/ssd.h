@@ -111,7 +111,8 @@ enum ssd_prof_class {
     SSD_PROF_OFF = -2, SSD_PROF_ALL = -1,
     SSD_PROF_GATE = 0, SSD_PROF_GEMM_QKV = 1, SSD_PROF_ATTN = 2, SSD_PROF_GEMM_O = 3,
     SSD_PROF_GEMM_GATE_UP = 4, SSD_PROF_GEMM_DOWN = 5, SSD_PROF_LMHEAD = 6, SSD_PROF_OTHER = 7,
-    SSD_PROF_N_CLASSES = 8
+    SSD_PROF_AR = 8,          /* one span per ar_fallback call */
+    SSD_PROF_N_CLASSES = 9
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
 /* Measurement aid: runs `iters` rounds of 8 independent v_mfma_f32_32x32x16_f16 per wavefront on
@@ -120,7 +121,8 @@ int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
  * and clock management leave for the matrix cores on this device.  Uses the first 256 KB of the
  * workspace and waits for the stream. */
 int ssd_measure_mfma_ceiling(ssd_ctx *ctx, int iters, float *tflops /*host*/, float *shader_ghz /*host*/);
-int ssd_profile_read(ssd_ctx *ctx, float *total_ms /*host [8]*/, int32_t *launches /*host [8]*/);
+int ssd_profile_read(ssd_ctx *ctx, float *total_ms /*host [SSD_PROF_N_CLASSES]*/,
+                     int32_t *launches /*host [SSD_PROF_N_CLASSES]*/);
 
 /* Sec. 2.1.  For every frame t of every utterance: softmax over the V_ctc scores (blank included),
  * entropy H_t in nats (Eq. 3, left side) and greedy label a_t = lowest-index argmax of the stored
@@ -149,6 +151,35 @@ int verify_forward(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_speec
                    const int32_t *prompt_ids, const int32_t *cu_prompt /*host*/,
                    const int32_t *draft_ids, const int32_t *cu_draft /*host*/, int Bv,
                    void *h_verify);
+
+/* The same pass, additionally storing the rotated keys and the values of every row of every layer
+ * into the K/V cache set with ssd_set_kv_cache, so that ar_fallback can continue from any prefix of
+ * the sequence: row `pos` of utterance b goes to cache slot kv_start[b] + pos.  kv_start: host [Bv];
+ * the slot ranges of different utterances must not overlap and should leave room for the tokens
+ * ar_fallback will append. */
+int verify_forward_kv(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_speech /*host*/,
+                      const int32_t *prompt_ids, const int32_t *cu_prompt /*host*/,
+                      const int32_t *draft_ids, const int32_t *cu_draft /*host*/, int Bv,
+                      const int32_t *kv_start /*host*/, void *h_verify);
+
+/* K/V cache for the auto-regressive fallback: a caller-owned dev buffer, 256-byte aligned, holding
+ * for every layer K [slots, n_kv_heads*head_dim] and V [slots, ...] in the activation type (IEEE half
+ * for SSD_BF16 models, fp32 for SSD_F32).  A NULL pointer detaches the cache. */
+size_t ssd_kv_cache_bytes(const ssd_ctx *ctx, int64_t slots);
+int ssd_set_kv_cache(ssd_ctx *ctx, void *dev_ptr, size_t bytes, int64_t slots);
+
+/* Sec. 2.3, Eq. 6: greedy auto-regressive continuation of Br utterances from their accepted
+ * prefixes.  Utterance b has ctx_len[b] = S + P + accept_len valid rows in the cache starting at slot
+ * kv_start[b] (written by verify_forward_kv; rows beyond the prefix are overwritten here).
+ * first_tok[b] (dev) is the token at position ctx_len[b]: the model's own choice after the prefix,
+ * which accept_prefix already delivers as greedy_tok at the first rejected draft position.
+ * Step t = 0..n_steps-1 feeds token u_t (u_0 = first_tok) at position ctx_len + t, appends its keys and
+ * values to the cache and writes u_{t+1} = lowest-index argmax of the next-token distribution to
+ * out_tokens[t * Br + b] (dev, [n_steps, Br]).  Stopping at an end-of-sequence token is the caller's
+ * business (truncate the row).  Needs ssd_ar_workspace_bytes(ctx, Br, n_steps) bytes of workspace. */
+size_t ssd_ar_workspace_bytes(const ssd_ctx *ctx, int max_utts, int max_steps);
+int ar_fallback(ssd_ctx *ctx, int Br, const int32_t *kv_start /*host [Br]*/, const int32_t *ctx_len /*host [Br]*/,
+                const int32_t *first_tok /*dev [Br]*/, int n_steps, int32_t *out_tokens /*dev [n_steps, Br]*/);
 
 /* Sec. 2.2-2.3 (Eq. 5, definition of j, Eq. 7).  draft_logp[r] = log softmax(lm_head . h_verify[r])
  * at token draft_ids[r]; the logits are never written to memory.  Token i passes iff

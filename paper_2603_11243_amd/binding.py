@@ -18,10 +18,12 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
            -5: "SSD_EUNSUPPORTED"}
 
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
-           "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix"]
+           "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix",
+           "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback"]
 
 PROF_OFF, PROF_ALL = -2, -1
-PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other"]
+PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
+                "ar_fallback"]
 
 
 class SsdError(RuntimeError):
@@ -72,6 +74,16 @@ def load_library() -> C.CDLL:
     lib.verify_forward.restype = i32
     lib.accept_prefix.argtypes = [vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
     lib.accept_prefix.restype = i32
+    lib.verify_forward_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.verify_forward_kv.restype = i32
+    lib.ssd_kv_cache_bytes.argtypes = [vp, i64]
+    lib.ssd_kv_cache_bytes.restype = C.c_size_t
+    lib.ssd_set_kv_cache.argtypes = [vp, vp, C.c_size_t, i64]
+    lib.ssd_set_kv_cache.restype = i32
+    lib.ssd_ar_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.ssd_ar_workspace_bytes.restype = C.c_size_t
+    lib.ar_fallback.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    lib.ar_fallback.restype = i32
     return lib
 
 
@@ -158,9 +170,11 @@ class Context:
     def workspace_bytes(self, max_frames=0, max_tokens=0, max_verify_rows=0, max_utts=0) -> int:
         return int(self._lib.ssd_workspace_bytes(self._h, max_frames, max_tokens, max_verify_rows, max_utts))
 
-    def reserve(self, max_frames=0, max_tokens=0, max_verify_rows=0, max_utts=0):
+    def reserve(self, max_frames=0, max_tokens=0, max_verify_rows=0, max_utts=0, ar_utts=0, ar_steps=0):
         """Allocates (through torch) and hands over a workspace big enough for the given maxima."""
         n = self.workspace_bytes(max_frames, max_tokens, max_verify_rows, max_utts)
+        if ar_utts and ar_steps:
+            n = max(n, int(self._lib.ssd_ar_workspace_bytes(self._h, ar_utts, ar_steps)))
         if self._ws is None or self._ws.numel() < n:
             self._ws = torch.empty(n, dtype=torch.uint8, device=self.device)
             self._check(self._lib.ssd_set_workspace(self._h, _ptr(self._ws), n))
@@ -206,13 +220,36 @@ class Context:
         return out
 
     def verify_forward(self, speech_emb: torch.Tensor, cu_speech, prompt_ids: torch.Tensor, cu_prompt,
-                       draft_ids: torch.Tensor, cu_draft, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                       draft_ids: torch.Tensor, cu_draft, out: Optional[torch.Tensor] = None,
+                       kv_start=None) -> torch.Tensor:
+        """kv_start (host ints, one per utterance): also store keys/values in the K/V cache (verify_forward_kv)."""
         cs, cp, cd = _host_i32(cu_speech), _host_i32(cu_prompt), _host_i32(cu_draft)
         Bv = len(cd) - 1
         if out is None:
             out = torch.empty((int(cd[-1]), self.cfg.d_model), dtype=self.act_dtype, device=self.device)
-        self._check(self._lib.verify_forward(self._h, _ptr(speech_emb), cs.ctypes.data, _ptr(prompt_ids),
-                                             cp.ctypes.data, _ptr(draft_ids), cd.ctypes.data, Bv, _ptr(out)))
+        if kv_start is None:
+            self._check(self._lib.verify_forward(self._h, _ptr(speech_emb), cs.ctypes.data, _ptr(prompt_ids),
+                                                 cp.ctypes.data, _ptr(draft_ids), cd.ctypes.data, Bv, _ptr(out)))
+        else:
+            ks = _host_i32(kv_start)
+            self._check(self._lib.verify_forward_kv(self._h, _ptr(speech_emb), cs.ctypes.data, _ptr(prompt_ids),
+                                                    cp.ctypes.data, _ptr(draft_ids), cd.ctypes.data, Bv,
+                                                    ks.ctypes.data, _ptr(out)))
+        return out
+
+    def set_kv_cache(self, slots: int):
+        """Allocates (through torch) a K/V cache of `slots` rows per layer and attaches it."""
+        n = int(self._lib.ssd_kv_cache_bytes(self._h, slots))
+        self._kv = torch.empty(n, dtype=torch.uint8, device=self.device)
+        self._check(self._lib.ssd_set_kv_cache(self._h, _ptr(self._kv), n, slots))
+
+    def ar_fallback(self, kv_start, ctx_len, first_tok: torch.Tensor, n_steps: int,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        ks, cl = _host_i32(kv_start), _host_i32(ctx_len)
+        Br = len(ks)
+        if out is None:
+            out = torch.empty((n_steps, Br), dtype=torch.int32, device=self.device)
+        self._check(self._lib.ar_fallback(self._h, Br, ks.ctypes.data, cl.ctypes.data, _ptr(first_tok), n_steps, _ptr(out)))
         return out
 
     def accept_prefix(self, h_verify: torch.Tensor, draft_ids: torch.Tensor, cu_draft, tau_slm: float,

@@ -92,6 +92,8 @@ struct ssd_ctx {
     float* rope_tab = nullptr;               // [max_positions][head_dim/2] (cos, sin) pairs
     void* ws = nullptr;
     size_t ws_bytes = 0;
+    void* kv = nullptr;                      // caller-owned K/V cache: [layer][K|V][slots][d_kv] in the activation type
+    int64_t kv_slots = 0;
     std::string err;
     Stager stager;
     Profiler prof;
@@ -164,7 +166,7 @@ GatePlan plan_gate(int64_t frames, int64_t utts) {
 int attn_tile_rows(int dtype) { return dtype == SSD_BF16 ? 128 : 4; }
 
 struct VerifyPlan {
-    size_t row_src, pos, vrow, tiles, meta_bytes;     // metadata block, uploaded in one copy
+    size_t row_src, pos, vrow, row_slot, tiles, meta_bytes;     // metadata block, uploaded in one copy
     size_t x, a, qkv, attn, gu, h, partials, total;   // activations
 };
 VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t utts) {
@@ -175,6 +177,7 @@ VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t ut
     p.row_src = o; o = align_up(o + (size_t)M * 4);
     p.pos = o; o = align_up(o + (size_t)M * 4);
     p.vrow = o; o = align_up(o + (size_t)Mv * 4);
+    p.row_slot = o; o = align_up(o + (size_t)M * 4);
     p.tiles = o; o = align_up(o + (size_t)max_tiles * sizeof(AttnTile));
     p.meta_bytes = o;
     const int64_t d = c.d_model, dq = (int64_t)c.n_q_heads * c.head_dim, dkv = (int64_t)c.n_kv_heads * c.head_dim;
@@ -456,8 +459,20 @@ int ctc_gate(ssd_ctx* ctx, const void* logits, int dtype, const int32_t* cu_fram
     return SSD_OK;
 }
 
-int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, const int32_t* prompt_ids,
-                   const int32_t* cu_prompt, const int32_t* draft_ids, const int32_t* cu_draft, int Bv, void* h_verify) {
+}  // extern "C"
+
+namespace {
+
+size_t kv_layer_bytes(const ssd_model_cfg& m, int64_t slots) {
+    return (size_t)slots * m.n_kv_heads * m.head_dim * elem_size(m.dtype);
+}
+// K cache and V cache of layer l
+void* kv_k(ssd_ctx* c, int l) { return static_cast<char*>(c->kv) + (size_t)(2 * l) * kv_layer_bytes(c->cfg, c->kv_slots); }
+void* kv_v(ssd_ctx* c, int l) { return static_cast<char*>(c->kv) + (size_t)(2 * l + 1) * kv_layer_bytes(c->cfg, c->kv_slots); }
+
+int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, const int32_t* prompt_ids,
+                const int32_t* cu_prompt, const int32_t* draft_ids, const int32_t* cu_draft, int Bv,
+                const int32_t* kv_start, void* h_verify) {
     if (!ctx) return SSD_EINVAL;
     if (!ctx->has_model) return fail(ctx, SSD_EINVAL, "verify_forward: context was created without a model");
     if (!cu_speech || !cu_prompt || !cu_draft) return fail(ctx, SSD_EINVAL, "verify_forward: NULL cu_* array");
@@ -476,7 +491,11 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
         if (S + P < 1) return fail(ctx, SSD_EINVAL, "verify_forward: utterance %d has no speech or prompt row", b);
         if (S + P + U > m.max_positions)
             return fail(ctx, SSD_ESHAPE, "verify_forward: utterance %d has %d rows, max_positions is %d", b, S + P + U, m.max_positions);
+        if (kv_start && (kv_start[b] < 0 || (int64_t)kv_start[b] + S + P + U > ctx->kv_slots))
+            return fail(ctx, SSD_EINVAL, "verify_forward_kv: utterance %d does not fit the K/V cache (start %d, %d rows, %lld slots)",
+                        b, kv_start[b], S + P + U, (long long)ctx->kv_slots);
     }
+    if (kv_start && !ctx->kv) return fail(ctx, SSD_EINVAL, "verify_forward_kv: no K/V cache set");
     const VerifyPlan p = plan_verify(m, M, Mv, Bv);
     if (!ctx->ws || ctx->ws_bytes < p.total)
         return fail(ctx, SSD_EWORKSPACE, "verify_forward: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
@@ -486,6 +505,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
     int32_t* row_src = reinterpret_cast<int32_t*>(meta.data() + p.row_src);
     int32_t* pos = reinterpret_cast<int32_t*>(meta.data() + p.pos);
     int32_t* vrow = reinterpret_cast<int32_t*>(meta.data() + p.vrow);
+    int32_t* row_slot = reinterpret_cast<int32_t*>(meta.data() + p.row_slot);
     AttnTile* tiles = reinterpret_cast<AttnTile*>(meta.data() + p.tiles);
     int n_tiles = 0;
     int64_t r = 0;
@@ -498,6 +518,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
         for (int i = 0; i < U; ++i, ++r) { row_src[r] = SRC_DRAFT | (cu_draft[b] + i); pos[r] = S + P + i; }
         // draft token i (1-based) is scored by sequence index S + P + i - 2
         for (int i = 1; i <= U; ++i) vrow[cu_draft[b] + i - 1] = start + S + P + i - 2;
+        if (kv_start) for (int i = 0; i < n; ++i) row_slot[start + i] = kv_start[b] + i;
         for (int q = 0; q < n; q += tile_rows) tiles[n_tiles++] = AttnTile{start, n, q, 0};
     }
     char* ws = static_cast<char*>(ctx->ws);
@@ -506,6 +527,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
     const int32_t* d_row_src = reinterpret_cast<const int32_t*>(ws + p.row_src);
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(ws + p.pos);
     const int32_t* d_vrow = reinterpret_cast<const int32_t*>(ws + p.vrow);
+    const int32_t* d_row_slot = reinterpret_cast<const int32_t*>(ws + p.row_slot);
     const AttnTile* d_tiles = reinterpret_cast<const AttnTile*>(ws + p.tiles);
     float* x = reinterpret_cast<float*>(ws + p.x);
     void* a = ws + p.a;
@@ -524,6 +546,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
         pending = 1;
         if (m.dtype == SSD_BF16) {
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st); }
+            if (kv_start) { ProfScope ps(ctx, SSD_PROF_OTHER); launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
             { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Mi, d, dq, ctx->ds_o[l], st); }
             { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
@@ -534,6 +557,7 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
             launch_rope_f32((float*)qkv, d_pos, ctx->rope_tab, Mi, m.n_q_heads + m.n_kv_heads, m.head_dim, dq + 2 * dkv, st);
+            if (kv_start) launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
             launch_attn_f32((const float*)qkv, (float*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, m.head_dim, st);
             launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Mi, d, dq, F32_ADD, st);
             launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, st);
@@ -544,6 +568,173 @@ int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speec
     }
     // verification rows only: final RMSNorm of the positions that score a draft token
     { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, partials, pending, split_stride, st); }
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+struct ArPlan {
+    size_t row_src, kv_start, pos, n_ctx, slot, meta_bytes;       // uploaded once: [Br], [Br], [steps][Br] x 3
+    size_t x, a, qkv, attn, gu, h, partials, hfin, logp, part_ms, tgt, part_arg, total;
+};
+ArPlan plan_ar(const ssd_model_cfg& c, int64_t Br, int64_t steps) {
+    ArPlan p;
+    const size_t es = elem_size(c.dtype);
+    const int64_t d = c.d_model, dq = (int64_t)c.n_q_heads * c.head_dim, dkv = (int64_t)c.n_kv_heads * c.head_dim;
+    size_t o = 0;
+    p.row_src = o; o = align_up(o + (size_t)Br * 4);
+    p.kv_start = o; o = align_up(o + (size_t)Br * 4);
+    p.pos = o; o = align_up(o + (size_t)(steps * Br) * 4);
+    p.n_ctx = o; o = align_up(o + (size_t)(steps * Br) * 4);
+    p.slot = o; o = align_up(o + (size_t)(steps * Br) * 4);
+    p.meta_bytes = o;
+    p.x = o; o = align_up(o + (size_t)(Br * d) * 4);
+    p.a = o; o = align_up(o + (size_t)(Br * d) * es);
+    p.qkv = o; o = align_up(o + (size_t)(Br * (dq + 2 * dkv)) * es);
+    p.attn = o; o = align_up(o + (size_t)(Br * dq) * es);
+    p.gu = o; if (c.dtype == SSD_F32) o = align_up(o + (size_t)(Br * 2 * c.d_ff) * 4);
+    p.h = o; o = align_up(o + (size_t)(Br * c.d_ff) * es);
+    p.partials = o; if (c.dtype == SSD_BF16 && Br <= SKINNY_MAX_ROWS) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * Br * d * 4);
+    p.hfin = o; o = align_up(o + (size_t)(Br * d) * es);
+    p.logp = o; o = align_up(o + (size_t)Br * 4);
+    p.part_ms = p.tgt = p.part_arg = o;
+    if (c.dtype == SSD_BF16) {
+        const int64_t g = lmhead_col_groups(c.vocab);
+        p.part_ms = o; o = align_up(o + (size_t)(g * Br) * sizeof(float2));
+        p.tgt = o; o = align_up(o + (size_t)Br * 4);
+        p.part_arg = o; o = align_up(o + (size_t)(g * Br) * sizeof(int2));
+    }
+    p.total = o;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int verify_forward(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, const int32_t* prompt_ids,
+                   const int32_t* cu_prompt, const int32_t* draft_ids, const int32_t* cu_draft, int Bv, void* h_verify) {
+    return verify_impl(ctx, speech_emb, cu_speech, prompt_ids, cu_prompt, draft_ids, cu_draft, Bv, nullptr, h_verify);
+}
+
+int verify_forward_kv(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, const int32_t* prompt_ids,
+                      const int32_t* cu_prompt, const int32_t* draft_ids, const int32_t* cu_draft, int Bv,
+                      const int32_t* kv_start, void* h_verify) {
+    if (ctx && !kv_start) return fail(ctx, SSD_EINVAL, "verify_forward_kv: NULL kv_start");
+    return verify_impl(ctx, speech_emb, cu_speech, prompt_ids, cu_prompt, draft_ids, cu_draft, Bv, kv_start, h_verify);
+}
+
+size_t ssd_kv_cache_bytes(const ssd_ctx* ctx, int64_t slots) {
+    if (!ctx || !ctx->has_model || slots <= 0) return 0;
+    return (size_t)2 * ctx->cfg.n_layers * kv_layer_bytes(ctx->cfg, slots);
+}
+
+int ssd_set_kv_cache(ssd_ctx* ctx, void* dev_ptr, size_t bytes, int64_t slots) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->has_model) return fail(ctx, SSD_EINVAL, "ssd_set_kv_cache: context was created without a model");
+    if (!dev_ptr || slots <= 0) { ctx->kv = nullptr; ctx->kv_slots = 0; return SSD_OK; }
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return fail(ctx, SSD_EINVAL, "K/V cache must be 256-byte aligned");
+    if (bytes < ssd_kv_cache_bytes(ctx, slots)) return fail(ctx, SSD_EWORKSPACE, "K/V cache of %zu bytes needed for %lld slots, %zu given",
+                                                            ssd_kv_cache_bytes(ctx, slots), (long long)slots, bytes);
+    ctx->kv = dev_ptr;
+    ctx->kv_slots = slots;
+    return SSD_OK;
+}
+
+size_t ssd_ar_workspace_bytes(const ssd_ctx* ctx, int max_utts, int max_steps) {
+    if (!ctx || !ctx->has_model || max_utts <= 0 || max_steps <= 0) return 0;
+    return plan_ar(ctx->cfg, max_utts, max_steps).total + 256;
+}
+
+int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ctx_len, const int32_t* first_tok,
+                int n_steps, int32_t* out_tokens) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->has_model) return fail(ctx, SSD_EINVAL, "ar_fallback: context was created without a model");
+    if (!kv_start || !ctx_len || !first_tok || !out_tokens) return fail(ctx, SSD_EINVAL, "ar_fallback: NULL argument");
+    if (Br <= 0 || n_steps <= 0) return fail(ctx, SSD_EINVAL, "ar_fallback: Br and n_steps must be positive");
+    if (!ctx->kv) return fail(ctx, SSD_EINVAL, "ar_fallback: no K/V cache set");
+    const ssd_model_cfg& m = ctx->cfg;
+    for (int b = 0; b < Br; ++b) {
+        if (ctx_len[b] < 1) return fail(ctx, SSD_EINVAL, "ar_fallback: utterance %d has an empty context", b);
+        if (ctx_len[b] + n_steps > m.max_positions)
+            return fail(ctx, SSD_ESHAPE, "ar_fallback: utterance %d would reach position %d, max_positions is %d", b, ctx_len[b] + n_steps, m.max_positions);
+        if (kv_start[b] < 0 || (int64_t)kv_start[b] + ctx_len[b] + n_steps > ctx->kv_slots)
+            return fail(ctx, SSD_EINVAL, "ar_fallback: utterance %d does not fit the K/V cache", b);
+    }
+    const ArPlan p = plan_ar(m, Br, n_steps);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "ar_fallback: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+    std::vector<char> meta(p.meta_bytes);
+    int32_t* row_src = reinterpret_cast<int32_t*>(meta.data() + p.row_src);
+    int32_t* h_kvs = reinterpret_cast<int32_t*>(meta.data() + p.kv_start);
+    int32_t* pos = reinterpret_cast<int32_t*>(meta.data() + p.pos);
+    int32_t* nctx = reinterpret_cast<int32_t*>(meta.data() + p.n_ctx);
+    int32_t* slot = reinterpret_cast<int32_t*>(meta.data() + p.slot);
+    for (int b = 0; b < Br; ++b) {
+        row_src[b] = SRC_DRAFT | b;
+        h_kvs[b] = kv_start[b];
+        for (int t = 0; t < n_steps; ++t) {
+            pos[(size_t)t * Br + b] = ctx_len[b] + t;               // position of the token fed at step t
+            nctx[(size_t)t * Br + b] = ctx_len[b] + t + 1;          // rows it attends to, itself included
+            slot[(size_t)t * Br + b] = kv_start[b] + ctx_len[b] + t;
+        }
+    }
+    char* ws = static_cast<char*>(ctx->ws);
+    int rc = upload(ctx, meta.data(), ws, p.meta_bytes);
+    if (rc != SSD_OK) return rc;
+    const int32_t* d_row_src = reinterpret_cast<const int32_t*>(ws + p.row_src);
+    const int32_t* d_kvs = reinterpret_cast<const int32_t*>(ws + p.kv_start);
+    float* x = reinterpret_cast<float*>(ws + p.x);
+    void* a = ws + p.a; void* qkv = ws + p.qkv; void* att = ws + p.attn; void* h = ws + p.h; void* hfin = ws + p.hfin;
+    float* partials = reinterpret_cast<float*>(ws + p.partials);
+    float* logp = reinterpret_cast<float*>(ws + p.logp);
+    hipStream_t st = ctx->stream;
+    const int d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
+    const int64_t split_stride = (int64_t)Br * d;
+    ProfScope ps_all(ctx, SSD_PROF_AR);
+    for (int t = 0; t < n_steps; ++t) {
+        const int32_t* tok_in = t == 0 ? first_tok : out_tokens + (size_t)(t - 1) * Br;
+        const int32_t* d_pos = reinterpret_cast<const int32_t*>(ws + p.pos) + (size_t)t * Br;
+        const int32_t* d_nctx = reinterpret_cast<const int32_t*>(ws + p.n_ctx) + (size_t)t * Br;
+        const int32_t* d_slot = reinterpret_cast<const int32_t*>(ws + p.slot) + (size_t)t * Br;
+        launch_embed_rows(m.dtype, nullptr, ctx->embed, nullptr, tok_in, d_row_src, Br, d, m.vocab, x, st);
+        int pending = 1;
+        for (int l = 0; l < m.n_layers; ++l) {
+            launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
+            pending = 1;
+            if (m.dtype == SSD_BF16) {
+                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l], st);
+                launch_kv_store(m.dtype, qkv, d_slot, Br, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
+                launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
+                pending = 1;
+                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], st);
+                pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], st);
+            } else {
+                float* gu = reinterpret_cast<float*>(ws + p.gu);
+                launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Br, dq + 2 * dkv, d, F32_STORE, st);
+                launch_rope_f32((float*)qkv, d_pos, ctx->rope_tab, Br, m.n_q_heads + m.n_kv_heads, m.head_dim, dq + 2 * dkv, st);
+                launch_kv_store(m.dtype, qkv, d_slot, Br, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
+                launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Br, d, dq, F32_ADD, st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, nullptr, 1, 0, st);
+                launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Br, 2 * m.d_ff, d, F32_STORE, st);
+                launch_swiglu_f32(gu, (float*)h, Br, m.d_ff, st);
+                launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Br, d, m.d_ff, F32_ADD, st);
+            }
+        }
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, nullptr, Br, d, m.rms_eps, hfin, partials, pending, split_stride, st);
+        int32_t* tok_out = out_tokens + (size_t)t * Br;
+        if (m.dtype == SSD_BF16) {
+            float2* part_ms = reinterpret_cast<float2*>(ws + p.part_ms);
+            float* tgt = reinterpret_cast<float*>(ws + p.tgt);
+            int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
+            launch_lmhead_mfma((const uint16_t*)hfin, (const uint16_t*)ctx->lm_head, tok_in, Br, d, m.vocab, part_ms, tgt, part_arg, true, ctx->ds_lm, st);
+            launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), Br, logp, tok_out, st);
+        } else {
+            launch_lmhead_f32((const float*)hfin, (const float*)ctx->lm_head, tok_in, Br, d, m.vocab, logp, tok_out, st);
+        }
+    }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }

@@ -1,0 +1,115 @@
+// Auto-regressive fallback (Sec. 2.3, Eq. 6): kernels that exist only for the token-by-token
+// continuation from the accepted prefix -- storing keys/values of the verification pass into a
+// cache, and attention of ONE new query row per utterance against its cached rows.
+// Everything else of a decode step reuses the verification kernels on a batch of Br rows
+// (RMSNorm, skinny weight-streaming GEMMs with split-K, LM head with argmax).
+#include "device_utils.h"
+#include "ssd_internal.h"
+
+namespace ssd {
+
+// ---------------------------------------------------------------------------------------------
+// Copy the (rotated) K and V parts of qkv rows into the cache of one layer.
+// qkv row layout: [q (d_q) | k (d_kv) | v (d_kv)]; cache: K [slots, d_kv], V [slots, d_kv].
+template <typename T>
+__global__ void __launch_bounds__(256) kv_store_kernel(const T* __restrict__ qkv, const int32_t* __restrict__ row_slot,
+                                                       int d_q, int d_kv, T* __restrict__ kc, T* __restrict__ vc) {
+    const int r = blockIdx.x;
+    const int64_t slot = row_slot[r];
+    if (slot < 0) return;
+    const T* src = qkv + (int64_t)r * (d_q + 2 * d_kv) + d_q;
+    constexpr int VEC = 16 / sizeof(T);
+    const uint4* ks = reinterpret_cast<const uint4*>(src);
+    const uint4* vs = reinterpret_cast<const uint4*>(src + d_kv);
+    uint4* kd = reinterpret_cast<uint4*>(kc + slot * d_kv);
+    uint4* vd = reinterpret_cast<uint4*>(vc + slot * d_kv);
+    for (int i = threadIdx.x; i < d_kv / VEC; i += 256) { kd[i] = ks[i]; vd[i] = vs[i]; }
+}
+
+void launch_kv_store(int dtype, const void* qkv, const int32_t* row_slot, int n_rows, int d_q, int d_kv, void* kc,
+                     void* vc, hipStream_t st) {
+    if (n_rows <= 0) return;
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(kv_store_kernel<f16_t>, dim3(n_rows), dim3(256), 0, st, (const f16_t*)qkv, row_slot, d_q, d_kv, (f16_t*)kc, (f16_t*)vc);
+    else
+        hipLaunchKernelGGL(kv_store_kernel<float>, dim3(n_rows), dim3(256), 0, st, (const float*)qkv, row_slot, d_q, d_kv, (float*)kc, (float*)vc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One query row per utterance: wavefront (b, head) attends to cache rows kv_start[b] .. +n_ctx[b]-1
+// (the last of which is the row of the query token itself, stored just before).
+// Keys are processed 64 at a time with an online softmax; lanes own keys for the scores and own
+// output dimensions for P.V.  head_dim <= 128, multiple of 8.
+template <typename T> __device__ __forceinline__ float elem_to_f32(T v);
+template <> __device__ __forceinline__ float elem_to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float elem_to_f32<f16_t>(f16_t v) { return f16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T f32_to_elem(float v);
+template <> __device__ __forceinline__ float f32_to_elem<float>(float v) { return v; }
+template <> __device__ __forceinline__ f16_t f32_to_elem<f16_t>(float v) { return f32_to_f16(v); }
+
+template <typename T>
+__global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ qkv, const T* __restrict__ kc,
+                                                         const T* __restrict__ vc, const int32_t* __restrict__ kv_start,
+                                                         const int32_t* __restrict__ n_ctx, int n_q_heads, int n_kv_heads,
+                                                         int head_dim, T* __restrict__ out) {
+    __shared__ float q_s[128];
+    __shared__ float p_s[64];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int kvh = h / (n_q_heads / n_kv_heads);
+    const int d_q = n_q_heads * head_dim, d_kv = n_kv_heads * head_dim;
+    const T* q = qkv + (int64_t)b * (d_q + 2 * d_kv) + h * head_dim;
+    for (int i = lane; i < head_dim; i += 64) q_s[i] = elem_to_f32<T>(q[i]);
+    __builtin_amdgcn_wave_barrier();
+    const int n = n_ctx[b];
+    const T* kbase = kc + (int64_t)kv_start[b] * d_kv + kvh * head_dim;
+    const T* vbase = vc + (int64_t)kv_start[b] * d_kv + kvh * head_dim;
+    const float scale = 1.0f / sqrtf((float)head_dim);
+    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int k0 = 0; k0 < n; k0 += 64) {
+        const int key = k0 + lane;
+        float s = -INFINITY;
+        if (key < n) {
+            const T* kr = kbase + (int64_t)key * d_kv;
+            float acc = 0.f;
+            for (int i = 0; i < head_dim; i += 8) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc = fmaf(q_s[i + e], elem_to_f32<T>(kr[i + e]), acc);
+            }
+            s = acc * scale;
+        }
+        const float m_new = fmaxf(m, group_allreduce<64>(s, OpMax()));
+        const float p = expf(s - m_new);
+        const float alpha = expf(m - m_new);
+        l = l * alpha + group_allreduce<64>(p, OpSum());
+        o0 *= alpha; o1 *= alpha;
+        p_s[lane] = p;
+        __builtin_amdgcn_wave_barrier();
+        const int n_keys = min(64, n - k0);
+        for (int j = 0; j < n_keys; ++j) {
+            const float pj = p_s[j];
+            const T* vr = vbase + (int64_t)(k0 + j) * d_kv;
+            if (lane < head_dim) o0 = fmaf(pj, elem_to_f32<T>(vr[lane]), o0);
+            if (lane + 64 < head_dim) o1 = fmaf(pj, elem_to_f32<T>(vr[lane + 64]), o1);
+        }
+        __builtin_amdgcn_wave_barrier();
+        m = m_new;
+    }
+    T* o = out + (int64_t)b * d_q + h * head_dim;
+    if (lane < head_dim) o[lane] = f32_to_elem<T>(o0 / l);
+    if (lane + 64 < head_dim) o[lane + 64] = f32_to_elem<T>(o1 / l);
+}
+
+void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
+                        const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
+                        hipStream_t st) {
+    if (Br <= 0) return;
+    if (dtype == SSD_BF16)
+        hipLaunchKernelGGL(decode_attn_kernel<f16_t>, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (f16_t*)out);
+    else
+        hipLaunchKernelGGL(decode_attn_kernel<float>, dim3(Br, n_q_heads), dim3(64), 0, st, (const float*)qkv, (const float*)kc,
+                           (const float*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (float*)out);
+}
+
+}  // namespace ssd

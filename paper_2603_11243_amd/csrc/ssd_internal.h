@@ -83,6 +83,14 @@ void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, 
 void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
                          hipStream_t st);
 
+// ---- ar_decode.hip (auto-regressive fallback): K/V cache of one layer is K [slots, d_kv], V [slots, d_kv]
+// in the activation type (IEEE half for bf16-stored models, fp32 otherwise); row_slot < 0 skips a row
+void launch_kv_store(int dtype, const void* qkv, const int32_t* row_slot, int n_rows, int d_q, int d_kv, void* kc,
+                     void* vc, hipStream_t st);
+void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
+                        const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
+                        hipStream_t st);
+
 // measurement aid: MFMA-only loop (sink: n_workgroups*256 floats, clocks: 2 x int64)
 void launch_mfma_ceiling(float* sink, long long* clocks, int n_workgroups, int iters, hipStream_t st);
 
