@@ -47,6 +47,18 @@ template <typename T> __device__ __forceinline__ T f32_to_elem(float v);
 template <> __device__ __forceinline__ float f32_to_elem<float>(float v) { return v; }
 template <> __device__ __forceinline__ f16_t f32_to_elem<f16_t>(float v) { return f32_to_f16(v); }
 
+// eight consecutive elements as fp32
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const f16_t* p, float (&v)[8]) {
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    const h8 a = *reinterpret_cast<const h8*>(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+
 template <typename T>
 __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ qkv, const T* __restrict__ kc,
                                                          const T* __restrict__ vc, const int32_t* __restrict__ kv_start,
@@ -65,7 +77,10 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
     const T* kbase = kc + (int64_t)kv_start[b] * d_kv + kvh * head_dim;
     const T* vbase = vc + (int64_t)kv_start[b] * d_kv + kvh * head_dim;
     const float scale = 1.0f / sqrtf((float)head_dim);
-    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    // P.V: lane = (key group kg of 4, chunk dc of 8 output dims)
+    const int kg = lane / 16, dc = lane % 16;
+    const bool dims_live = dc * 8 < head_dim;
+    float m = -INFINITY, l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < n; k0 += 64) {
         const int key = k0 + lane;
         float s = -INFINITY;
@@ -73,8 +88,10 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
             const T* kr = kbase + (int64_t)key * d_kv;
             float acc = 0.f;
             for (int i = 0; i < head_dim; i += 8) {
+                float kv8[8];
+                load8(kr + i, kv8);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc = fmaf(q_s[i + e], elem_to_f32<T>(kr[i + e]), acc);
+                for (int e = 0; e < 8; ++e) acc = fmaf(q_s[i + e], kv8[e], acc);
             }
             s = acc * scale;
         }
@@ -82,22 +99,34 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
         const float p = expf(s - m_new);
         const float alpha = expf(m - m_new);
         l = l * alpha + group_allreduce<64>(p, OpSum());
-        o0 *= alpha; o1 *= alpha;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= alpha;
         p_s[lane] = p;
         __builtin_amdgcn_wave_barrier();
         const int n_keys = min(64, n - k0);
-        for (int j = 0; j < n_keys; ++j) {
-            const float pj = p_s[j];
-            const T* vr = vbase + (int64_t)(k0 + j) * d_kv;
-            if (lane < head_dim) o0 = fmaf(pj, elem_to_f32<T>(vr[lane]), o0);
-            if (lane + 64 < head_dim) o1 = fmaf(pj, elem_to_f32<T>(vr[lane + 64]), o1);
+        if (dims_live) {
+            for (int j = kg; j < n_keys; j += 4) {
+                const float pj = p_s[j];
+                float v8[8];
+                load8(vbase + (int64_t)(k0 + j) * d_kv + dc * 8, v8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, v8[e], o[e]);
+            }
         }
         __builtin_amdgcn_wave_barrier();
         m = m_new;
     }
-    T* o = out + (int64_t)b * d_q + h * head_dim;
-    if (lane < head_dim) o[lane] = f32_to_elem<T>(o0 / l);
-    if (lane + 64 < head_dim) o[lane + 64] = f32_to_elem<T>(o1 / l);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        o[e] += __shfl_xor(o[e], 16);
+        o[e] += __shfl_xor(o[e], 32);
+    }
+    if (kg == 0 && dims_live) {
+        T* dst = out + (int64_t)b * d_q + h * head_dim + dc * 8;
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e] = f32_to_elem<T>(o[e] * inv);
+    }
 }
 
 void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
