@@ -181,6 +181,30 @@ size_t ssd_ar_workspace_bytes(const ssd_ctx *ctx, int max_utts, int max_steps);
 int ar_fallback(ssd_ctx *ctx, int Br, const int32_t *kv_start /*host [Br]*/, const int32_t *ctx_len /*host [Br]*/,
                 const int32_t *first_tok /*dev [Br]*/, int n_steps, int32_t *out_tokens /*dev [n_steps, Br]*/);
 
+/* Sec. 3.2-3.3: operating points.  Frame entropies and token likelihoods do not depend on the
+ * thresholds, so the decisions for a whole grid of (tau_CTC, tau_SLM) come from one gate pass and one
+ * verification pass.  tau arrays are host arrays; outputs are dev, threshold-major:
+ * gate_pass[a*B + b] = max_entropy[b] < tau_ctc[a];  accept_len / all_accepted[a*Bv + b] as in
+ * accept_prefix with tau_slm[a].  The ablations of Sec. 3.3 are caller policy on these outputs:
+ * gate only = skip the verification calls; verification only = verify every utterance and ignore
+ * gate_pass.  Both calls use a few hundred bytes at the start of the workspace. */
+int ssd_gate_grid(ssd_ctx *ctx, const float *max_entropy /*dev [B]*/, int B, const float *tau_ctc /*host*/, int n_tau,
+                  uint8_t *gate_pass /*dev [n_tau, B]*/);
+int ssd_accept_grid(ssd_ctx *ctx, const float *draft_logp /*dev*/, const int32_t *cu_draft /*host*/, int Bv,
+                    const float *tau_slm /*host*/, int n_tau, int32_t *accept_len /*dev [n_tau, Bv]*/,
+                    uint8_t *all_accepted /*dev [n_tau, Bv]*/);
+
+/* Sec. 3.2: length-sorted adaptive batching under a token budget (the paper uses 50K).  Host only,
+ * no context.  lengths[i] > 0 is the row count of utterance i (CTC frames for the gate phase,
+ * speech + prompt + draft rows for verification, context rows for the fallback phase: the phases
+ * are batched separately).  Utterances are taken longest first (ties: lower index first) and added to
+ * the current batch while its cost stays <= max_tokens; cost = sum of lengths (packed rows, what this
+ * library runs) or, with padded != 0, size x longest member (what a padded implementation pays).
+ * An utterance longer than the budget forms a batch of its own.  Outputs: order[n] (utterance
+ * indices in batch order), batch_start[n_batches + 1] (needs room for n + 1 entries), n_batches. */
+int ssd_plan_batches(const int32_t *lengths, int n, int64_t max_tokens, int padded, int32_t *order,
+                     int32_t *batch_start, int32_t *n_batches);
+
 /* Sec. 2.2-2.3 (Eq. 5, definition of j, Eq. 7).  draft_logp[r] = log softmax(lm_head . h_verify[r])
  * at token draft_ids[r]; the logits are never written to memory.  Token i passes iff
  * draft_logp > ln(tau_slm), evaluated in fp32 with ln(tau_slm) rounded from double (tau_slm <= 0

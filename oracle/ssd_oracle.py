@@ -281,6 +281,41 @@ def accept_prefix(logp: Sequence[float], tau_slm: float) -> Dict:
     return {"accept_len": n_acc, "all_accepted": n_acc == U}
 
 
+def threshold_grid(max_entropy: Sequence[float], logps: List[Sequence[float]], taus_ctc: Sequence[float],
+                   taus_slm: Sequence[float]) -> Dict:
+    """Decisions for a grid of operating points (Sec. 3.2: tau_CTC in [0.7, 3.0], tau_SLM in {0.1, 0.2}).
+    Frame entropies and token likelihoods do not depend on the thresholds, so every grid point is the
+    single-threshold rule applied to the same numbers."""
+    gate = np.array([[bool(h < t) for h in max_entropy] for t in taus_ctc], dtype=bool).reshape(len(taus_ctc), len(max_entropy))
+    acc = np.array([[accept_prefix(lp, t)["accept_len"] for lp in logps] for t in taus_slm], dtype=np.int32).reshape(len(taus_slm), len(logps))
+    full = np.array([[accept_prefix(lp, t)["all_accepted"] for lp in logps] for t in taus_slm], dtype=bool).reshape(len(taus_slm), len(logps))
+    return {"gate_pass": gate, "accept_len": acc, "all_accepted": full}
+
+
+def plan_batches(lengths: Sequence[int], max_tokens: int, padded: bool) -> List[List[int]]:
+    """Length-sorted adaptive batching under a token budget (Sec. 3.2).
+
+    Utterances are taken longest first (ties: lower index first) and appended to the current batch
+    while the batch stays within max_tokens; the cost of a batch is the sum of its lengths (packed
+    rows) or, with padded=True, its size times its longest member.  A single utterance longer than
+    the budget forms a batch of its own.  Returns lists of utterance indices.
+    """
+    order = sorted(range(len(lengths)), key=lambda i: (-int(lengths[i]), i))
+    batches: List[List[int]] = []
+    cur: List[int] = []
+    for i in order:
+        cand = cur + [i]
+        cost = (len(cand) * max(int(lengths[k]) for k in cand)) if padded else sum(int(lengths[k]) for k in cand)
+        if cur and cost > max_tokens:
+            batches.append(cur)
+            cur = [i]
+        else:
+            cur = cand
+    if cur:
+        batches.append(cur)
+    return batches
+
+
 def final_hypothesis_case(gate_pass: bool, all_accepted: bool) -> str:
     """Case split of Eq. 7 (Sec. 2.3): the draft is final if Eq. 3 or Eq. 5 holds, otherwise
     the accepted prefix is continued auto-regressively."""

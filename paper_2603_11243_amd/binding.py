@@ -19,7 +19,8 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
 
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix",
-           "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback"]
+           "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
+           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
@@ -84,6 +85,12 @@ def load_library() -> C.CDLL:
     lib.ssd_ar_workspace_bytes.restype = C.c_size_t
     lib.ar_fallback.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     lib.ar_fallback.restype = i32
+    lib.ssd_gate_grid.argtypes = [vp, vp, i32, vp, i32, vp]
+    lib.ssd_gate_grid.restype = i32
+    lib.ssd_accept_grid.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.ssd_accept_grid.restype = i32
+    lib.ssd_plan_batches.argtypes = [vp, i32, i64, i32, vp, vp, vp]
+    lib.ssd_plan_batches.restype = i32
     return lib
 
 
@@ -237,6 +244,23 @@ class Context:
                                                     ks.ctypes.data, _ptr(out)))
         return out
 
+    def gate_grid(self, max_entropy: torch.Tensor, taus_ctc) -> torch.Tensor:
+        t = np.ascontiguousarray(np.asarray(taus_ctc, dtype=np.float32))
+        B = int(max_entropy.numel())
+        out = torch.empty((len(t), B), dtype=torch.uint8, device=self.device)
+        self._check(self._lib.ssd_gate_grid(self._h, _ptr(max_entropy), B, t.ctypes.data, len(t), _ptr(out)))
+        return out
+
+    def accept_grid(self, draft_logp: torch.Tensor, cu_draft, taus_slm) -> dict:
+        t = np.ascontiguousarray(np.asarray(taus_slm, dtype=np.float32))
+        cd = _host_i32(cu_draft)
+        Bv = len(cd) - 1
+        out = {"accept_len": torch.empty((len(t), Bv), dtype=torch.int32, device=self.device),
+               "all_accepted": torch.empty((len(t), Bv), dtype=torch.uint8, device=self.device)}
+        self._check(self._lib.ssd_accept_grid(self._h, _ptr(draft_logp), cd.ctypes.data, Bv, t.ctypes.data, len(t),
+                                              _ptr(out["accept_len"]), _ptr(out["all_accepted"])))
+        return out
+
     def set_kv_cache(self, slots: int):
         """Allocates (through torch) a K/V cache of `slots` rows per layer and attaches it."""
         n = int(self._lib.ssd_kv_cache_bytes(self._h, slots))
@@ -267,3 +291,17 @@ class Context:
                                             _ptr(out["draft_logp"]), _ptr(out["accept_len"]),
                                             _ptr(out["all_accepted"]), _ptr(out.get("greedy_tok"))))
         return out
+
+
+def plan_batches(lengths, max_tokens: int, padded: bool = False):
+    """Host-only batch planner (ssd_plan_batches): returns a list of index arrays, one per batch."""
+    L = _host_i32(lengths)
+    n = len(L)
+    order = np.empty(n, dtype=np.int32)
+    start = np.empty(n + 1, dtype=np.int32)
+    nb = C.c_int32()
+    rc = lib().ssd_plan_batches(L.ctypes.data, n, int(max_tokens), int(padded), order.ctypes.data, start.ctypes.data,
+                                C.byref(nb))
+    if rc != 0:
+        raise SsdError(rc, "ssd_plan_batches: bad argument")
+    return [order[start[k]:start[k + 1]].copy() for k in range(nb.value)]

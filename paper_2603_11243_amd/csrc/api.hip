@@ -401,6 +401,71 @@ int ssd_profile_read(ssd_ctx* ctx, float* total_ms, int32_t* launches) {
     return SSD_OK;
 }
 
+int ssd_gate_grid(ssd_ctx* ctx, const float* max_entropy, int B, const float* tau_ctc, int n_tau, uint8_t* gate_pass) {
+    if (!ctx) return SSD_EINVAL;
+    if (!max_entropy || !tau_ctc || !gate_pass || B <= 0 || n_tau <= 0) return fail(ctx, SSD_EINVAL, "ssd_gate_grid: bad argument");
+    const size_t need = align_up((size_t)n_tau * 4);
+    if (!ctx->ws || ctx->ws_bytes < need) return fail(ctx, SSD_EWORKSPACE, "ssd_gate_grid: workspace of %zu bytes needed", need);
+    int rc = upload(ctx, tau_ctc, ctx->ws, (size_t)n_tau * 4);
+    if (rc != SSD_OK) return rc;
+    launch_gate_grid(max_entropy, B, static_cast<const float*>(ctx->ws), n_tau, gate_pass, ctx->stream);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int ssd_accept_grid(ssd_ctx* ctx, const float* draft_logp, const int32_t* cu_draft, int Bv, const float* tau_slm, int n_tau,
+                    int32_t* accept_len, uint8_t* all_accepted) {
+    if (!ctx) return SSD_EINVAL;
+    if (!cu_draft || !tau_slm || !accept_len || !all_accepted || Bv <= 0 || n_tau <= 0)
+        return fail(ctx, SSD_EINVAL, "ssd_accept_grid: bad argument");
+    if (!check_cu(cu_draft, Bv, false)) return fail(ctx, SSD_EINVAL, "ssd_accept_grid: cu_draft must start at 0 and be non-decreasing");
+    if (cu_draft[Bv] && !draft_logp) return fail(ctx, SSD_EINVAL, "ssd_accept_grid: NULL draft_logp");
+    const size_t off_tau = align_up((size_t)(Bv + 1) * 4);
+    const size_t need = off_tau + align_up((size_t)n_tau * 4);
+    if (!ctx->ws || ctx->ws_bytes < need) return fail(ctx, SSD_EWORKSPACE, "ssd_accept_grid: workspace of %zu bytes needed", need);
+    std::vector<char> meta(need);
+    memcpy(meta.data(), cu_draft, (size_t)(Bv + 1) * 4);
+    float* ln_taus = reinterpret_cast<float*>(meta.data() + off_tau);
+    for (int a = 0; a < n_tau; ++a) {
+        if (tau_slm[a] != tau_slm[a]) return fail(ctx, SSD_EINVAL, "ssd_accept_grid: tau_slm[%d] is NaN", a);
+        ln_taus[a] = tau_slm[a] > 0.f ? (float)log((double)tau_slm[a]) : -INFINITY;
+    }
+    char* ws = static_cast<char*>(ctx->ws);
+    int rc = upload(ctx, meta.data(), ws, need);
+    if (rc != SSD_OK) return rc;
+    launch_accept_grid(draft_logp, reinterpret_cast<const int32_t*>(ws), Bv, reinterpret_cast<const float*>(ws + off_tau), n_tau,
+                       accept_len, all_accepted, ctx->stream);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int ssd_plan_batches(const int32_t* lengths, int n, int64_t max_tokens, int padded, int32_t* order, int32_t* batch_start,
+                     int32_t* n_batches) {
+    if (!lengths || !order || !batch_start || !n_batches || n <= 0 || max_tokens <= 0) return SSD_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        if (lengths[i] <= 0) return SSD_EINVAL;
+        order[i] = i;
+    }
+    std::stable_sort(order, order + n, [&](int32_t a, int32_t b) { return lengths[a] > lengths[b]; });   // longest first
+    int nb = 0;
+    int64_t count = 0, sum = 0, longest = 0;
+    batch_start[0] = 0;
+    for (int k = 0; k < n; ++k) {
+        const int64_t len = lengths[order[k]];
+        const int64_t c2 = count + 1, s2 = sum + len, l2 = std::max(longest, len);
+        const int64_t cost = padded ? c2 * l2 : s2;
+        if (count > 0 && cost > max_tokens) {
+            batch_start[++nb] = k;
+            count = 1; sum = len; longest = len;
+        } else {
+            count = c2; sum = s2; longest = l2;
+        }
+    }
+    batch_start[++nb] = n;
+    *n_batches = nb;
+    return SSD_OK;
+}
+
 int ssd_measure_mfma_ceiling(ssd_ctx* ctx, int iters, float* tflops, float* shader_ghz) {
     if (!ctx || !tflops || !shader_ghz || iters <= 0) return SSD_EINVAL;
     const int n_wg = 256;                                  // one workgroup of four wavefronts per CU

@@ -304,6 +304,41 @@ __global__ void __launch_bounds__(64) accept_scan_kernel(const float* __restrict
     }
 }
 
+// Operating-point grids (Sec. 3.2): entropies and likelihoods do not depend on the thresholds, so the
+// decisions for n thresholds are n applications of the single-threshold rule to the same numbers.
+__global__ void __launch_bounds__(256) gate_grid_kernel(const float* __restrict__ max_entropy, int B,
+                                                        const float* __restrict__ taus, int n_tau,
+                                                        uint8_t* __restrict__ gate_pass) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= B * n_tau) return;
+    gate_pass[i] = max_entropy[i % B] < taus[i / B] ? 1 : 0;
+}
+
+__global__ void __launch_bounds__(64) accept_grid_kernel(const float* __restrict__ logp, const int32_t* __restrict__ cu_draft,
+                                                         int Bv, const float* __restrict__ ln_taus,
+                                                         int32_t* __restrict__ accept_len, uint8_t* __restrict__ all_accepted) {
+    const int b = blockIdx.x, a = blockIdx.y;
+    const int lo = cu_draft[b], U = cu_draft[b + 1] - lo;
+    const float ln_tau = ln_taus[a];
+    int first_fail = U;
+    for (int i = threadIdx.x; i < U; i += 64) {
+        if (!(logp[lo + i] > ln_tau)) { first_fail = i; break; }
+    }
+    first_fail = group_allreduce_i<64>(first_fail, OpMinI());
+    if (threadIdx.x == 0) {
+        accept_len[a * Bv + b] = first_fail;
+        all_accepted[a * Bv + b] = first_fail == U ? 1 : 0;
+    }
+}
+
+void launch_gate_grid(const float* max_entropy, int B, const float* taus_dev, int n_tau, uint8_t* gate_pass, hipStream_t st) {
+    hipLaunchKernelGGL(gate_grid_kernel, dim3((B * n_tau + 255) / 256), dim3(256), 0, st, max_entropy, B, taus_dev, n_tau, gate_pass);
+}
+void launch_accept_grid(const float* logp, const int32_t* cu_draft_dev, int Bv, const float* ln_taus_dev, int n_tau,
+                        int32_t* accept_len, uint8_t* all_accepted, hipStream_t st) {
+    hipLaunchKernelGGL(accept_grid_kernel, dim3(Bv, n_tau), dim3(64), 0, st, logp, cu_draft_dev, Bv, ln_taus_dev, accept_len, all_accepted);
+}
+
 void launch_accept_scan(const float* logp, const int32_t* cu_draft_dev, int Bv, float ln_tau, int32_t* accept_len,
                         uint8_t* all_accepted, hipStream_t st) {
     if (Bv <= 0) return;

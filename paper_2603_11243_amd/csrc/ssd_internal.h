@@ -91,6 +91,11 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
                         const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
                         hipStream_t st);
 
+// threshold grids: outputs are [n_tau][B] / [n_tau][Bv]
+void launch_gate_grid(const float* max_entropy, int B, const float* taus_dev, int n_tau, uint8_t* gate_pass, hipStream_t st);
+void launch_accept_grid(const float* logp, const int32_t* cu_draft_dev, int Bv, const float* ln_taus_dev, int n_tau,
+                        int32_t* accept_len, uint8_t* all_accepted, hipStream_t st);
+
 // measurement aid: MFMA-only loop (sink: n_workgroups*256 floats, clocks: 2 x int64)
 void launch_mfma_ceiling(float* sink, long long* clocks, int n_workgroups, int iters, hipStream_t st);
 

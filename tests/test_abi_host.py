@@ -71,3 +71,26 @@ def test_create_rejects_bad_model(lib):
     cfg = ModelCfgC(2, 256, 4, 4, 64, 1024, 4096, 1e-5, 10000.0, 0, 512)       # fine shape, NULL weights
     assert lib.ssd_create(C.byref(h), C.byref(cfg), C.byref(w), None) == -1
     assert lib.ssd_create(C.byref(h), C.byref(cfg), None, None) == -1
+
+
+def test_plan_batches_matches_oracle(lib):
+    """The batch planner is host code: compared with the oracle here, no GPU involved."""
+    from oracle import ssd_oracle as O
+    from paper_2603_11243_amd.binding import plan_batches
+    rng = np.random.default_rng(21)
+    for padded in (False, True):
+        for _ in range(100):
+            n = int(rng.integers(1, 40))
+            L = rng.integers(1, 800, size=n)
+            budget = int(rng.integers(100, 5000))
+            got = [list(map(int, b)) for b in plan_batches(L, budget, padded)]
+            assert got == O.plan_batches(L, budget, padded)
+    # the paper's budget on a corpus-like length mix (frames of 1-30 s utterances)
+    L = np.rint(rng.uniform(1, 30, size=500) * 25).astype(np.int32)
+    got = plan_batches(L, 50000, False)
+    assert [list(map(int, b)) for b in got] == O.plan_batches(L, 50000, False)
+    assert all(L[b].sum() <= 50000 for b in got) and sum(len(b) for b in got) == 500
+    h = C.c_int32()
+    assert lib.ssd_plan_batches(None, 3, 10, 0, None, None, C.byref(h)) == -1
+    bad = np.array([3, 0, 2], dtype=np.int32); o = np.empty(3, np.int32); s = np.empty(4, np.int32)
+    assert lib.ssd_plan_batches(bad.ctypes.data, 3, 10, 0, o.ctypes.data, s.ctypes.data, C.byref(h)) == -1

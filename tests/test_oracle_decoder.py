@@ -262,3 +262,43 @@ def test_final_hypothesis_case_split():
     assert O.final_hypothesis_case(False, True) == "draft"
     assert O.final_hypothesis_case(True, True) == "draft"
     assert O.final_hypothesis_case(False, False) == "prefix+ar"
+
+
+def test_threshold_grid_matches_single_thresholds_and_is_monotone():
+    rng = np.random.default_rng(12)
+    H = rng.uniform(0.0, 5.0, size=9)
+    H[3] = GOLD["tau_ctc_high_accuracy"]                      # equality at a grid point must fail
+    lps = [-rng.exponential(1.5, size=int(rng.integers(0, 9))) for _ in range(7)]
+    tc = [GOLD["tau_ctc_high_accuracy"], 1.5, GOLD["tau_ctc_high_rtfx"]]
+    ts = [GOLD["tau_slm_high_rtfx"], GOLD["tau_slm_high_accuracy"]]
+    g = O.threshold_grid(H, lps, tc, ts)
+    assert g["gate_pass"].shape == (3, 9) and g["accept_len"].shape == (2, 7)
+    assert not g["gate_pass"][0, 3] and g["gate_pass"][1, 3]
+    for a, t in enumerate(tc):
+        assert list(g["gate_pass"][a]) == [h < t for h in H]
+    assert (g["gate_pass"][0] <= g["gate_pass"][2]).all()                      # a looser gate accepts more
+    assert (g["accept_len"][0] >= g["accept_len"][1]).all()                    # a stricter likelihood accepts less
+    for b, lp in enumerate(lps):
+        for a, t in enumerate(ts):
+            assert g["accept_len"][a, b] == next((i for i in range(len(lp)) if math.exp(lp[i]) <= t), len(lp))
+
+
+def test_plan_batches_properties_and_brute_force():
+    rng = np.random.default_rng(13)
+    for padded in (False, True):
+        for _ in range(50):
+            n = int(rng.integers(1, 12))
+            L = rng.integers(1, 40, size=n)
+            budget = int(rng.integers(10, 120))
+            bs = O.plan_batches(L, budget, padded)
+            flat = [i for b in bs for i in b]
+            assert sorted(flat) == list(range(n))                               # a partition
+            assert [L[i] for i in flat] == sorted(L, reverse=True)              # longest first
+            cost = lambda b: len(b) * max(L[i] for i in b) if padded else sum(L[i] for i in b)
+            for k, b in enumerate(bs):
+                assert cost(b) <= budget or len(b) == 1
+                if k + 1 < len(bs):                                             # greedy: the next utterance did not fit
+                    assert cost(b + [bs[k + 1][0]]) > budget
+    # the paper's setting: a 50K budget swallows a small sorted batch whole
+    assert O.plan_batches([300, 100, 200], 50000, False) == [[0, 2, 1]]
+    assert O.plan_batches([30, 10, 20], 45, True) == [[0], [2, 1]]
