@@ -164,6 +164,29 @@ def test_bf16_reduced_depth_whole_batch(name, layers, B):
     print(f"{wl.name}: worst |dlogp| = {worst:.3e} over {vi.cu_draft[-1]} tokens")
 
 
+@pytest.mark.parametrize("M", [33, 128, 129, 191, 257, 513, 770])
+def test_bf16_row_counts_around_tile_and_split_thresholds(M):
+    """One 1B-width layer; utterance lengths chosen so that the total row count M sits on and next to
+    the boundaries the GEMM dispatch uses (skinny path up to 128 rows, tile heights 128/192/256)."""
+    from workloads.synth import VerifyInputs
+    wl = scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=1, B=3)
+    w = make_model_weights(wl.model, 4242, device="cuda")
+    rng = np.random.default_rng(M)
+    n = [M // 3, M // 3, M - 2 * (M // 3)]
+    U = [max(1, k // 3) for k in n]
+    P = [min(4, k - u - 1) for k, u in zip(n, U)]
+    S = [k - u - p for k, u, p in zip(n, U, P)]
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    g = torch.Generator(device="cuda").manual_seed(M)
+    sp = (torch.randn(sum(S), wl.model.d_model, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    vi = VerifyInputs(sp, cu(S), rng.integers(0, wl.model.vocab, sum(P)).astype(np.int32), cu(P),
+                      rng.integers(0, wl.model.vocab, sum(U)).astype(np.int32), cu(U))
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    worst = _compare(wl, w, vi, res, tau)
+    assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a dropped tile would be O(1)
+
+
 # ------------------------------------------------------------------ bf16, full depth, sampled utterances
 
 @pytest.mark.parametrize("name,n_sample", [("cfg2_1b_b1", 1), ("cfg3_1b_ragged64", 2), ("cfg4_1b_long_ml", 1),
