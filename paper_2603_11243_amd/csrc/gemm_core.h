@@ -144,14 +144,31 @@ struct GemmTile {
         if (n >= NSTAGE) __builtin_amdgcn_s_waitcnt(WAIT_KEEP_NO_LGKM); else __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         read_frags(0, 0, a0, b0);
+        // The compiler's scheduler would sink every fragment read to just before its first use; the
+        // pattern below pins "one MFMA, one LDS read" so that the reads of step kk+1 are spread under
+        // the MFMAs of step kk.
+        auto interleave = [&]() {
+#pragma unroll
+            for (int q = 0; q < TM * TN; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+                if (q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one DS read
+            }
+        };
         int stage = 0;
         for (int i = 0; i < n; ++i) {
+            __builtin_amdgcn_sched_barrier(0);
             read_frags(stage, 1, a1, b1);
             mfma_block(a0, b0);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
             read_frags(stage, 2, a0, b0);
             mfma_block(a1, b1);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
             read_frags(stage, 3, a1, b1);
             mfma_block(a0, b0);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
             // all reads of `stage` are issued; wait for them and for slice i+1 (its loads are the oldest)
             if (i + NSTAGE < n + 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP); else __builtin_amdgcn_s_waitcnt(0x0070);
             __syncthreads();
