@@ -2,8 +2,9 @@
 // This is the mechanism that lets Eq. 5 be evaluated for all draft tokens in one forward (Sec. 2.2):
 // position p only attends to positions <= p of its own utterance.
 //
-// A workgroup of 4 wavefronts owns 128 query positions of one (utterance, query head); each
-// wavefront owns 32 of them.  Keys/values are visited in blocks of 64 with an online softmax.
+// A workgroup owns 64 query positions of one (utterance, KV head): 2 x RATIO wavefronts, one per
+// (query head of the group, 32-row block), so that a K/V block is staged once for every query head
+// that shares it.  Keys/values are visited in blocks of 64 with an online softmax.
 //   S^T[key, q]  = K . Q^T      (A operand: K rows from LDS, B operand: Q rows held in registers)
 //   O^T[dim, q] += V^T . P^T    (A operand: V^T rows from LDS, B operand: P^T)
 // Working with the transposed products keeps a query position in one lane column (lane%32) for
@@ -21,23 +22,26 @@ constexpr int ATT_KB = 64;                    // keys per block
 constexpr int ATT_K_STRIDE = ATT_HD + 8;      // Ks[key][dim], elements
 constexpr int ATT_V_STRIDE = ATT_KB + 8;      // Vt[dim][slot], elements
 
-__global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
-                                                        const AttnTile* __restrict__ tiles, int n_q_heads,
-                                                        int n_kv_heads) {
+template <int RATIO>      // query heads per KV head
+__global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
+                                                                const AttnTile* __restrict__ tiles, int n_q_heads,
+                                                                int n_kv_heads) {
+    constexpr int NT = 128 * RATIO;
+    constexpr int STAGE_ITERS = (ATT_KB * 16 + NT - 1) / NT;      // 16-byte chunks of a 64 x 128 block per thread
     __shared__ __align__(16) f16_t Ks[ATT_KB * ATT_K_STRIDE];
     __shared__ __align__(16) f16_t Vt[ATT_HD * ATT_V_STRIDE];
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int hgrp = lane / 32, lcol = lane % 32;
     const AttnTile t = tiles[blockIdx.x];
-    const int head = blockIdx.y;
-    const int kvh = head / (n_q_heads / n_kv_heads);
+    const int kvh = blockIdx.y;
+    const int head = kvh * RATIO + wave / 2;
     const int d_q = n_q_heads * ATT_HD, d_kv = n_kv_heads * ATT_HD;
     const int ldq = d_q + 2 * d_kv;
     const f16_t* seq = qkv + (int64_t)t.seq_start * ldq;
     const f16_t* kbase = seq + d_q + kvh * ATT_HD;
     const f16_t* vbase = kbase + d_kv;
 
-    const int q_first = t.q_start + wave * 32;          // first query position of this wavefront
+    const int q_first = t.q_start + (wave % 2) * 32;    // first query position of this wavefront
     const int qpos = q_first + lcol;
     const bool wave_live = q_first < t.seq_len;
 
@@ -57,36 +61,40 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict_
     float m_run = -INFINITY, l_run = 0.f;
     const float sc = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(128)
 
-    const int kv_end = min(t.seq_len, t.q_start + 128);             // keys needed by this tile
+    const int kv_end = min(t.seq_len, t.q_start + 64);              // keys needed by this tile
     // K/V blocks go global -> registers -> LDS; the registers of block kb+1 are loaded while block kb
     // is being multiplied.  K: thread owns (key = c/16, 8 dims) -> coalesced rows.  V: thread owns
     // (key = tid%64, 8 dims) so that a wavefront writes 64 neighbouring keys of one V^T row.
-    uint4 k_reg[4], v_reg[4];
+    uint4 k_reg[STAGE_ITERS], v_reg[STAGE_ITERS];
     auto load_kv = [&](int kb) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int c = tid + it * 256;
-            const int krow = min(kb + c / 16, t.seq_len - 1);
-            k_reg[it] = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + (c % 16) * 8);
-            const int vrow = min(kb + tid % 64, t.seq_len - 1);
-            v_reg[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)vrow * ldq + (tid / 64 + 4 * it) * 8);
+        for (int it = 0; it < STAGE_ITERS; ++it) {
+            const int c = tid + it * NT;
+            if (c < ATT_KB * 16) {
+                const int krow = min(kb + c / 16, t.seq_len - 1);
+                k_reg[it] = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + (c % 16) * 8);
+                const int vrow = min(kb + c % 64, t.seq_len - 1);
+                v_reg[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)vrow * ldq + (c / 64) * 8);
+            }
         }
     };
     load_kv(0);
     for (int kb = 0; kb < kv_end; kb += ATT_KB) {
         // ---- stage K (row-major) and V (transposed, permuted) blocks
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int c = tid + it * 256;
-            *reinterpret_cast<uint4*>(Ks + (c / 16) * ATT_K_STRIDE + (c % 16) * 8) = k_reg[it];
-            const int key = tid % 64, dc = tid / 64 + 4 * it;
-            const uint4 vv = v_reg[it];
-            const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
-            f16_t* vd = Vt + (dc * 8) * ATT_V_STRIDE + slot;
-            vd[0 * ATT_V_STRIDE] = (f16_t)(vv.x & 0xffff); vd[1 * ATT_V_STRIDE] = (f16_t)(vv.x >> 16);
-            vd[2 * ATT_V_STRIDE] = (f16_t)(vv.y & 0xffff); vd[3 * ATT_V_STRIDE] = (f16_t)(vv.y >> 16);
-            vd[4 * ATT_V_STRIDE] = (f16_t)(vv.z & 0xffff); vd[5 * ATT_V_STRIDE] = (f16_t)(vv.z >> 16);
-            vd[6 * ATT_V_STRIDE] = (f16_t)(vv.w & 0xffff); vd[7 * ATT_V_STRIDE] = (f16_t)(vv.w >> 16);
+        for (int it = 0; it < STAGE_ITERS; ++it) {
+            const int c = tid + it * NT;
+            if (c < ATT_KB * 16) {
+                *reinterpret_cast<uint4*>(Ks + (c / 16) * ATT_K_STRIDE + (c % 16) * 8) = k_reg[it];
+                const int key = c % 64, dc = c / 64;
+                const uint4 vv = v_reg[it];
+                const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
+                f16_t* vd = Vt + (dc * 8) * ATT_V_STRIDE + slot;
+                vd[0 * ATT_V_STRIDE] = (f16_t)(vv.x & 0xffff); vd[1 * ATT_V_STRIDE] = (f16_t)(vv.x >> 16);
+                vd[2 * ATT_V_STRIDE] = (f16_t)(vv.y & 0xffff); vd[3 * ATT_V_STRIDE] = (f16_t)(vv.y >> 16);
+                vd[4 * ATT_V_STRIDE] = (f16_t)(vv.z & 0xffff); vd[5 * ATT_V_STRIDE] = (f16_t)(vv.z >> 16);
+                vd[6 * ATT_V_STRIDE] = (f16_t)(vv.w & 0xffff); vd[7 * ATT_V_STRIDE] = (f16_t)(vv.w >> 16);
+            }
         }
         if (kb + ATT_KB < kv_end) load_kv(kb + ATT_KB);
         __syncthreads();
@@ -177,8 +185,12 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(const f16_t* __restrict_
 void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
                       int n_kv_heads, hipStream_t st) {
     if (n_tiles <= 0) return;
-    hipLaunchKernelGGL(attn_mfma_kernel, dim3(n_tiles, n_q_heads), dim3(256), 0, st, qkv, out, tiles, n_q_heads,
-                       n_kv_heads);
+    const int ratio = n_q_heads / n_kv_heads;
+    const dim3 grid(n_tiles, n_kv_heads);
+    if (ratio == 1) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(128), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else if (ratio == 2) hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else if (ratio == 3) hipLaunchKernelGGL(attn_mfma_kernel<3>, grid, dim3(384), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else hipLaunchKernelGGL(attn_mfma_kernel<4>, grid, dim3(512), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
 }
 
 }  // namespace ssd
