@@ -55,8 +55,8 @@ enum ssd_dtype { SSD_F32 = 0, SSD_BF16 = 1 };
  * exactly, to half times a per-tensor power of two.  Activations beyond the half range (|v| >
  * 65504 after RMSNorm or in the MLP) are not supported.
  * Supported: head_dim 128 (bf16) or any multiple of 4 up to 128 (f32); n_q_heads a multiple of
- * n_kv_heads (at most 4 times for bf16); for bf16 d_model, (n_q_heads + 2 n_kv_heads)*head_dim and vocab multiples of 256,
- * d_ff a multiple of 128; for f32 d_model, d_ff, n_q_heads*head_dim multiples of 16 and d_model <= 1024. */
+ * n_kv_heads (at most 4 times for bf16); for bf16 d_model (<= 8192), (n_q_heads + 2 n_kv_heads)*head_dim
+ * and vocab multiples of 256, d_ff a multiple of 128; for f32 d_model, d_ff, n_q_heads*head_dim multiples of 16 and d_model <= 1024. */
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
     float   rms_eps, rope_theta;

@@ -217,6 +217,7 @@ int check_model(ssd_ctx* c, const ssd_model_cfg& m) {
     const int dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
     if (m.dtype == SSD_BF16) {
         if (m.head_dim != 128) return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs head_dim 128 (got %d)", m.head_dim);
+        if (m.d_model > 8192) return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs d_model <= 8192");
         if (m.n_q_heads / m.n_kv_heads > 4) return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs at most 4 query heads per KV head");
         if (m.d_model % 256 || m.d_ff % 128 || dq % 128 || dkv % 128 || (dq + 2 * dkv) % 256 || m.vocab % 256)
             return fail(c, SSD_ESHAPE, "ssd_create: bf16 needs d_model, n_q_heads*head_dim + 2*n_kv_heads*head_dim and vocab to be "

@@ -52,55 +52,65 @@ void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, con
 // RMSNorm: out[r] = x[row] * gain / sqrt(mean(x[row]^2) + eps), row = row_idx ? row_idx[r] : r.
 // One wavefront per row; statistics in fp32.  d must be a multiple of 4.
 // T = bf16 gain with f16 output (MFMA operand type), or fp32 gain with fp32 output.
-template <typename T>
+template <typename T, int NV>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                       const int32_t* __restrict__ row_idx, int n_rows, int d,
                                                       float eps, T* __restrict__ out, const float* __restrict__ partials,
                                                       int n_splits, int64_t split_stride) {
+    // the row stays in registers between the statistic and the scaling: NV float4 per lane (d <= 256*NV)
     const int lane = threadIdx.x % 64;
     const int r = blockIdx.x * 4 + threadIdx.x / 64;
     if (r >= n_rows) return;
     const int64_t row = row_idx ? row_idx[r] : r;
     float4* src = reinterpret_cast<float4*>(x + row * d);
     const int n4 = d / 4;
-    float ss = 0.f;
+    float4 v[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = lane + 64 * j;
+        v[j] = i < n4 ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     if (n_splits > 1) {
         // pending K-split partial sums of the projection before this norm: add them in split order
-        for (int i = lane; i < n4; i += 64) {
-            float4 v = src[i];
-            for (int s = 0; s < n_splits; ++s) {
-                const float4 p = reinterpret_cast<const float4*>(partials + s * split_stride + row * d)[i];
-                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        for (int s = 0; s < n_splits; ++s) {
+            const float4* ps = reinterpret_cast<const float4*>(partials + s * split_stride + row * d);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int i = lane + 64 * j;
+                if (i < n4) {
+                    const float4 p = ps[i];
+                    v[j].x += p.x; v[j].y += p.y; v[j].z += p.z; v[j].w += p.w;
+                }
             }
-            if (!row_idx) src[i] = v;
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         }
-    } else {
-        for (int i = lane; i < n4; i += 64) {
-            const float4 v = src[i];
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        if (!row_idx) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int i = lane + 64 * j;
+                if (i < n4) src[i] = v[j];
+            }
         }
     }
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
     ss = group_allreduce<64>(ss, OpSum());
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     T* dst = out + (int64_t)r * d;
-    for (int i = lane; i < n4; i += 64) {
-        float4 v = src[i];
-        if (n_splits > 1 && row_idx) {           // gathered rows are not written back: redo the sum
-            for (int s = 0; s < n_splits; ++s) {
-                const float4 p = reinterpret_cast<const float4*>(partials + s * split_stride + row * d)[i];
-                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-            }
-        }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = lane + 64 * j;
+        if (i >= n4) continue;
         if constexpr (sizeof(T) == 2) {
             const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
             uint2 o;
-            o.x = pack_f16x2(v.x * inv * bf16_lo(g.x), v.y * inv * bf16_hi(g.x));
-            o.y = pack_f16x2(v.z * inv * bf16_lo(g.y), v.w * inv * bf16_hi(g.y));
+            o.x = pack_f16x2(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x));
+            o.y = pack_f16x2(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y));
             reinterpret_cast<uint2*>(dst)[i] = o;
         } else {
             const float4 g = reinterpret_cast<const float4*>(gain)[i];
-            reinterpret_cast<float4*>(dst)[i] = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+            reinterpret_cast<float4*>(dst)[i] =
+                make_float4(v[j].x * inv * g.x, v[j].y * inv * g.y, v[j].z * inv * g.z, v[j].w * inv * g.w);
         }
     }
 }
@@ -170,11 +180,17 @@ void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_id
             hipLaunchKernelGGL((rmsnorm_row_kernel<float, 4>), dim3(n_rows), dim3(256), 0, st, x, (const float*)gain, row_idx, d, eps, (float*)out, partials, n_splits, split_stride);
         return;
     }
-    const unsigned grid = (unsigned)((n_rows + 3) / 4);
-    if (dtype == SSD_BF16)
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, n_rows, d, eps, (bf16_t*)out, partials, n_splits, split_stride);
-    else
-        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(grid), dim3(256), 0, st, x, (const float*)gain, row_idx, n_rows, d, eps, (float*)out, partials, n_splits, split_stride);
+    const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
+#define SSD_RMSNORM(T, NV) \
+    hipLaunchKernelGGL((rmsnorm_kernel<T, NV>), grid, block, 0, st, x, (const T*)gain, row_idx, n_rows, d, eps, (T*)out, partials, n_splits, split_stride)
+    if (dtype == SSD_BF16) {
+        if (d <= 2048) SSD_RMSNORM(bf16_t, 8);
+        else if (d <= 4096) SSD_RMSNORM(bf16_t, 16);
+        else SSD_RMSNORM(bf16_t, 32);          // d_model <= 8192 is checked at context creation
+    } else {
+        SSD_RMSNORM(float, 4);                 // fp32 models have d_model <= 1024
+    }
+#undef SSD_RMSNORM
 }
 
 // ---------------------------------------------------------------------------------------------
