@@ -22,6 +22,7 @@
 // Rows >= M are clamped on load and must be skipped by the epilogue.
 // Requirements: N % BN == 0, K % 64 == 0, A and W 16-byte aligned and smaller than 4 GiB.
 #pragma once
+#include <type_traits>
 #include "device_utils.h"
 
 namespace ssd {
@@ -130,6 +131,9 @@ struct GemmTile {
         // and the last MFMA block, so the first fragment read of the next slice and the global
         // loads that refill the freed stage are issued before that MFMA block and overlap with it.
         constexpr int KK = GEMM_BK / 16;
+        constexpr int HALF = TM * TN / 2;
+        constexpr int LOADS_PER_MFMA = (A_LOADS + B_LOADS + HALF - 1) / HALF;
+        constexpr int READS_PER_MFMA = (TM + TN + HALF - 1) / HALF;
         static_assert(KK == 4, "pipeline below is written for four k-steps per slice");
         static_assert(NSTAGE >= 2 && (NSTAGE - 2) * (A_LOADS + B_LOADS) <= 63, "vmcnt range");
         // s_waitcnt immediates: lgkmcnt(0) with vmcnt(V): V low 4 bits in [3:0], high 2 bits in [15:14]
@@ -154,8 +158,13 @@ struct GemmTile {
                 if (q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one DS read
             }
         };
+        // One slice.  STEADY: the slice NSTAGE ahead exists, so the refill loads and the first fragment
+        // read of the next slice are unconditional and sit in one basic block with the last MFMA
+        // block, where the pattern spreads them: issued as one burst by every wavefront right after
+        // the barrier, the loads queue up in the address path and hold back the MFMAs behind them.
         int stage = 0;
-        for (int i = 0; i < n; ++i) {
+        auto slice = [&](auto steady, int i) {
+            constexpr bool STEADY = decltype(steady)::value;
             __builtin_amdgcn_sched_barrier(0);
             read_frags(stage, 1, a1, b1);
             mfma_block(a0, b0);
@@ -170,14 +179,30 @@ struct GemmTile {
             interleave();
             __builtin_amdgcn_sched_barrier(0);
             // all reads of `stage` are issued; wait for them and for slice i+1 (its loads are the oldest)
-            if (i + NSTAGE < n + 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP); else __builtin_amdgcn_s_waitcnt(0x0070);
-            __syncthreads();
-            if (i + NSTAGE < n) issue_loads(kt0 + i + NSTAGE, stage);
             const int next = (stage + 1 == NSTAGE) ? 0 : stage + 1;
-            if (i + 1 < n) read_frags(next, 0, a0, b0);
-            mfma_block(a1, b1);
+            if constexpr (STEADY) {
+                __builtin_amdgcn_s_waitcnt(WAIT_KEEP);
+                __syncthreads();
+                issue_loads(kt0 + i + NSTAGE, stage);
+                read_frags(next, 0, a0, b0);
+                mfma_block(a1, b1);
+#pragma unroll
+                for (int q = 0; q < TM * TN; ++q) {     // loads under the first half, fragment reads under the second
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (q < HALF) __builtin_amdgcn_sched_group_barrier(0x010, LOADS_PER_MFMA, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, READS_PER_MFMA, 0);
+                }
+            } else {
+                if (i + NSTAGE < n + 1) __builtin_amdgcn_s_waitcnt(WAIT_KEEP); else __builtin_amdgcn_s_waitcnt(0x0070);
+                __syncthreads();
+                if (i + 1 < n) read_frags(next, 0, a0, b0);
+                mfma_block(a1, b1);
+            }
             stage = next;
-        }
+        };
+        int i = 0;
+        for (; i + NSTAGE < n; ++i) slice(std::true_type(), i);
+        for (; i < n; ++i) slice(std::false_type(), i);
     }
 };
 
