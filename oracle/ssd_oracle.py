@@ -98,6 +98,26 @@ def ctc_gate(logits: np.ndarray, cu_frames: Sequence[int], blank: int, tau_ctc: 
             "gate_pass": gate, "drafts": drafts}
 
 
+# --------------------------------------------------------------------------- CTC output layer
+
+def ctc_head_logits(enc_h, w_ctc, bias=None) -> np.ndarray:
+    """Scores of the CTC output layer (Sec. 3.1: the encoder's 1024-wide states feed an output
+    layer over the 348 CTC symbols): z_t = W h_t + b.
+
+    enc_h: [T, d_enc], w_ctc: [V, d_enc], bias: [V] or None.  Stored values widened exactly to
+    float64; one library matrix product.
+    """
+    z = _f64(enc_h) @ _f64(w_ctc).T
+    if bias is not None:
+        z = z + _f64(bias)[None, :]
+    return z
+
+
+def ctc_head_gate(enc_h, w_ctc, bias, cu_frames: Sequence[int], blank: int, tau_ctc: float) -> Dict:
+    """Eqs. 2-3 evaluated on the scores of the output layer (never rounded to a storage type)."""
+    return ctc_gate(ctc_head_logits(enc_h, w_ctc, bias), cu_frames, blank, tau_ctc)
+
+
 # ------------------------------------------------------------------------ decoder
 
 def rmsnorm(x: np.ndarray, w: np.ndarray, eps: float) -> np.ndarray:

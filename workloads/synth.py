@@ -8,6 +8,7 @@ Small tensors (CTC logits, ids, lengths) come from numpy PCG64 streams; large
 tensors (decoder weights, speech embeddings) come from torch generators so they
 can be drawn directly on an accelerator and copied back for the oracle.
 """
+import math
 from dataclasses import dataclass
 from typing import List, Optional
 
@@ -85,6 +86,60 @@ def make_ctc_batch(wl: Workload, seed: Optional[int] = None) -> CtcBatch:
         z[rows, path] += boost
     logits = torch.from_numpy(z).to(_TORCH_DTYPE[wl.model.dtype])
     return CtcBatch(logits, cu, seconds, confident, toks_all, path_all)
+
+
+@dataclass
+class CtcHeadBatch:
+    enc_h: torch.Tensor           # [sum_T, d_enc] encoder output states, storage dtype, CPU
+    w_ctc: torch.Tensor           # [V_ctc, d_enc] output-layer weight, storage dtype
+    bias: torch.Tensor            # [V_ctc] fp32
+    cu_frames: np.ndarray         # int32 [B+1]
+    confident: np.ndarray         # bool [B]
+    planted_path: np.ndarray      # int32 [sum_T]
+
+
+def make_ctc_head_batch(wl: Workload, d_enc: int = 1024, V_ctc: Optional[int] = None,
+                        seed: Optional[int] = None) -> CtcHeadBatch:
+    """Encoder states and an output layer whose logits look like make_ctc_batch's.
+
+    W rows are N(0, 1/d_enc) (unit norm on average), bias N(0, 0.1^2).  A frame's state is unit
+    Gaussian noise plus boost * W[y] / |W[y]|^2 for its planted symbol y, so its logits are ~N(0,1)
+    noise with the planted symbol raised by `boost` (16 for confident utterances, 8 or 5 otherwise).
+    """
+    seed = wl.seed if seed is None else seed
+    V = wl.V_ctc if V_ctc is None else V_ctc
+    r_len, r_tok, r_noise, r_w = _rng(seed, 11), _rng(seed, 12), _rng(seed, 13), _rng(seed, 14)
+    lo, hi = wl.seconds
+    seconds = r_len.uniform(lo, hi, size=wl.B) if hi > lo else np.full(wl.B, lo)
+    T = np.maximum(1, np.rint(seconds * wl.frames_per_s).astype(np.int64))
+    n_conf = int(round(wl.gate_rate * wl.B))
+    confident = np.zeros(wl.B, dtype=bool)
+    if n_conf:
+        confident[r_len.choice(wl.B, size=n_conf, replace=False)] = True
+    cu = np.zeros(wl.B + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(T)
+    dt = _TORCH_DTYPE[wl.model.dtype]
+    w = (r_w.standard_normal((V, d_enc)) / math.sqrt(d_enc)).astype(np.float32)
+    w = torch.from_numpy(w).to(dt)
+    wf = w.float().numpy()
+    unit = wf / (wf * wf).sum(axis=1, keepdims=True)
+    bias = torch.from_numpy((0.1 * r_w.standard_normal(V)).astype(np.float32))
+    h = r_noise.standard_normal((int(cu[-1]), d_enc), dtype=np.float32)
+    path_all = np.empty(int(cu[-1]), dtype=np.int32)
+    for b in range(wl.B):
+        if wl.draft_tokens[0] >= 0:
+            U = int(r_tok.integers(wl.draft_tokens[0], wl.draft_tokens[1] + 1))
+        else:
+            U = int(round(wl.draft_per_s * seconds[b]))
+        _, path = _plant_alignment(r_tok, int(T[b]), U, V, min(wl.blank_id, V - 1))
+        path_all[cu[b]:cu[b + 1]] = path
+        n = len(path)
+        if confident[b]:
+            boost = np.full(n, 16.0, dtype=np.float32)
+        else:
+            boost = np.where(r_noise.random(n) < 0.6, 8.0, 5.0).astype(np.float32)
+        h[cu[b]:cu[b + 1]] += boost[:, None] * unit[path]
+    return CtcHeadBatch(torch.from_numpy(h).to(dt), w, bias, cu, confident, path_all)
 
 
 def make_ctc_to_llm_map(wl: Workload, seed: Optional[int] = None) -> np.ndarray:
