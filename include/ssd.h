@@ -112,7 +112,8 @@ enum ssd_prof_class {
     SSD_PROF_GATE = 0, SSD_PROF_GEMM_QKV = 1, SSD_PROF_ATTN = 2, SSD_PROF_GEMM_O = 3,
     SSD_PROF_GEMM_GATE_UP = 4, SSD_PROF_GEMM_DOWN = 5, SSD_PROF_LMHEAD = 6, SSD_PROF_OTHER = 7,
     SSD_PROF_AR = 8,          /* one span per ar_fallback call */
-    SSD_PROF_N_CLASSES = 9
+    SSD_PROF_CTC_HEAD = 9,    /* one span per ctc_head_gate call */
+    SSD_PROF_N_CLASSES = 10
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
 /* Measurement aid: runs `iters` rounds of 8 independent v_mfma_f32_32x32x16_f16 per wavefront on
@@ -138,6 +139,23 @@ int ctc_gate(ssd_ctx *ctx, const void *logits, int dtype, const int32_t *cu_fram
              float *frame_entropy, int32_t *frame_argmax,
              float *max_entropy /*dev [B]*/, uint8_t *gate_pass /*dev [B]*/,
              int32_t *draft_ctc /*dev [cu_frames[B]]*/, int32_t *draft_len /*dev [B]*/);
+
+/* Sec. 3.1 (output layer of the CTC encoder: 1024-wide states, 348 symbols) feeding Sec. 2.1.
+ * ssd_set_ctc_head copies the output layer into the context (zero-padded to a multiple of 256
+ * symbols; the caller's arrays may be released on return; a second call replaces the first).
+ * w_ctc: dev [V_ctc, d_enc] bfloat16 row-major; bias: dev [V_ctc] fp32 or NULL (zero);
+ * d_enc a multiple of 64, V_ctc <= 65536.  Allocates device memory; waits for the stream.
+ *
+ * ctc_head_gate evaluates z[t, v] = enc_h[t] . w_ctc[v] + bias[v] and, on those scores, exactly what
+ * ctc_gate defines (Eqs. 2-3 and the collapse B) with the same outputs.  The scores are formed in
+ * fp32 from the stored bf16 operands and are never rounded or written to memory; the argmax is taken
+ * on the fp32 scores (lowest index among equal ones).
+ * enc_h: dev [cu_frames[B], d_enc] bfloat16 packed rows.  Other arguments as for ctc_gate.
+ * Errors: SSD_EINVAL (no output layer set, NULL or inconsistent arguments), SSD_EWORKSPACE. */
+int ssd_set_ctc_head(ssd_ctx *ctx, const void *w_ctc, const float *bias, int V_ctc, int d_enc);
+int ctc_head_gate(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*host*/, int B, int blank_id,
+                  float tau_ctc, float *frame_entropy, int32_t *frame_argmax, float *max_entropy,
+                  uint8_t *gate_pass, int32_t *draft_ctc, int32_t *draft_len);
 
 /* Sec. 2.2 (Eq. 4; parallel scoring through the causal mask).  For each of the Bv utterances that
  * did not pass the gate, runs the decoder over the rows [speech_emb rows; embed[prompt ids];

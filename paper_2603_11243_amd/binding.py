@@ -20,11 +20,11 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
-           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches"]
+           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
-                "ar_fallback"]
+                "ar_fallback", "ctc_head_gate"]
 
 
 class SsdError(RuntimeError):
@@ -91,6 +91,10 @@ def load_library() -> C.CDLL:
     lib.ssd_accept_grid.restype = i32
     lib.ssd_plan_batches.argtypes = [vp, i32, i64, i32, vp, vp, vp]
     lib.ssd_plan_batches.restype = i32
+    lib.ssd_set_ctc_head.argtypes = [vp, vp, vp, i32, i32]
+    lib.ssd_set_ctc_head.restype = i32
+    lib.ctc_head_gate.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, vp, vp, vp]
+    lib.ctc_head_gate.restype = i32
     return lib
 
 
@@ -224,6 +228,38 @@ class Context:
                                        blank_id, tau_ctc, _ptr(out.get("frame_entropy")),
                                        _ptr(out.get("frame_argmax")), _ptr(out["max_entropy"]),
                                        _ptr(out["gate_pass"]), _ptr(out["draft_ctc"]), _ptr(out["draft_len"])))
+        return out
+
+    def set_ctc_head(self, w_ctc: torch.Tensor, bias: Optional[torch.Tensor] = None):
+        """Output layer of the CTC encoder: w_ctc [V_ctc, d_enc] bf16, bias [V_ctc] fp32 (both on the device)."""
+        if w_ctc.dtype != torch.bfloat16 or not w_ctc.is_contiguous():
+            raise ValueError("w_ctc must be a contiguous bfloat16 tensor")
+        if bias is not None and (bias.dtype != torch.float32 or bias.numel() != w_ctc.shape[0]):
+            raise ValueError("bias must be float32 [V_ctc]")
+        self._check(self._lib.ssd_set_ctc_head(self._h, _ptr(w_ctc), _ptr(bias), int(w_ctc.shape[0]), int(w_ctc.shape[1])))
+        self._head_shape = (int(w_ctc.shape[0]), int(w_ctc.shape[1]))
+
+    def ctc_head_gate(self, enc_h: torch.Tensor, cu_frames, blank_id: int, tau_ctc: float,
+                      want_frames: bool = False) -> dict:
+        cu = _host_i32(cu_frames)
+        B, n_rows = len(cu) - 1, int(enc_h.shape[0])
+        if enc_h.dtype != torch.bfloat16 or not enc_h.is_contiguous():
+            raise ValueError("enc_h must be a contiguous bfloat16 tensor")
+        shape = getattr(self, "_head_shape", None)
+        if shape is not None and int(enc_h.shape[1]) != shape[1]:
+            raise ValueError(f"enc_h has {enc_h.shape[1]} columns, the output layer expects {shape[1]}")
+        dev = self.device
+        out = {"max_entropy": torch.empty(max(B, 0), dtype=torch.float32, device=dev),
+               "gate_pass": torch.empty(max(B, 0), dtype=torch.uint8, device=dev),
+               "draft_ctc": torch.empty(n_rows, dtype=torch.int32, device=dev),
+               "draft_len": torch.empty(max(B, 0), dtype=torch.int32, device=dev)}
+        if want_frames:
+            out["frame_entropy"] = torch.empty(n_rows, dtype=torch.float32, device=dev)
+            out["frame_argmax"] = torch.empty(n_rows, dtype=torch.int32, device=dev)
+        self._check(self._lib.ctc_head_gate(self._h, _ptr(enc_h), cu.ctypes.data, B, blank_id, tau_ctc,
+                                            _ptr(out.get("frame_entropy")), _ptr(out.get("frame_argmax")),
+                                            _ptr(out["max_entropy"]), _ptr(out["gate_pass"]),
+                                            _ptr(out["draft_ctc"]), _ptr(out["draft_len"])))
         return out
 
     def verify_forward(self, speech_emb: torch.Tensor, cu_speech, prompt_ids: torch.Tensor, cu_prompt,

@@ -92,6 +92,9 @@ struct ssd_ctx {
     float* rope_tab = nullptr;               // [max_positions][head_dim/2] (cos, sin) pairs
     void* ws = nullptr;
     size_t ws_bytes = 0;
+    uint16_t* head_w = nullptr;              // CTC output layer, rows padded with zeros to a multiple of 256
+    float* head_bias = nullptr;
+    int head_V = 0, head_V_pad = 0, head_d = 0;
     void* kv = nullptr;                      // caller-owned K/V cache: [layer][K|V][slots][d_kv] in the activation type
     int64_t kv_slots = 0;
     std::string err;
@@ -159,6 +162,18 @@ GatePlan plan_gate(int64_t frames, int64_t utts) {
     p.H = o; o = align_up(o + (size_t)frames * 4);
     p.arg = o; o = align_up(o + (size_t)frames * 4);
     p.cu = o; o = align_up(o + (size_t)(utts + 1) * 4);
+    p.total = o;
+    return p;
+}
+
+struct HeadPlan { size_t H, arg, cu, part, total; };
+HeadPlan plan_head(int64_t frames, int64_t utts, int V) {
+    HeadPlan p;
+    size_t o = 0;
+    p.H = o; o = align_up(o + (size_t)frames * 4);
+    p.arg = o; o = align_up(o + (size_t)frames * 4);
+    p.cu = o; o = align_up(o + (size_t)(utts + 1) * 4);
+    p.part = o; o = align_up(o + (size_t)frames * ctc_head_groups(V) * sizeof(float4));
     p.total = o;
     return p;
 }
@@ -362,6 +377,7 @@ size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_t
                            int64_t max_utts) {
     if (!ctx || max_frames < 0 || max_tokens < 0 || max_verify_rows < 0 || max_utts < 0) return 0;
     size_t need = plan_gate(max_frames, max_utts).total;
+    if (ctx->head_V) need = std::max(need, plan_head(max_frames, max_utts, ctx->head_V).total);
     if (ctx->has_model) {
         need = std::max(need, plan_verify(ctx->cfg, max_tokens, max_verify_rows, max_utts).total);
         need = std::max(need, plan_accept(ctx->cfg, max_verify_rows, max_utts).total);
@@ -521,6 +537,74 @@ int ctc_gate(ssd_ctx* ctx, const void* logits, int dtype, const int32_t* cu_fram
         ProfScope ps(ctx, SSD_PROF_GATE);
         launch_gate(logits, dtype, n_rows, V_ctc, cu_dev, B, blank_id, tau_ctc, H, arg, max_entropy, gate_pass, draft_ctc,
                     draft_len, ctx->stream);
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int ssd_set_ctc_head(ssd_ctx* ctx, const void* w_ctc, const float* bias, int V_ctc, int d_enc) {
+    if (!ctx) return SSD_EINVAL;
+    if (!w_ctc) return fail(ctx, SSD_EINVAL, "ssd_set_ctc_head: NULL weight");
+    if (V_ctc <= 0 || d_enc <= 0) return fail(ctx, SSD_EINVAL, "ssd_set_ctc_head: non-positive size");
+    if (d_enc % 64) return fail(ctx, SSD_ESHAPE, "ssd_set_ctc_head: d_enc must be a multiple of 64 (got %d)", d_enc);
+    if (V_ctc > 65536) return fail(ctx, SSD_ESHAPE, "ssd_set_ctc_head: at most 65536 symbols");
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    auto drop = [&](void* p) {
+        if (!p) return;
+        for (auto& q : ctx->owned) if (q == p) q = nullptr;
+        (void)hipFree(p);
+    };
+    drop(ctx->head_w); drop(ctx->head_bias);
+    ctx->head_w = nullptr; ctx->head_bias = nullptr; ctx->head_V = 0;
+    const int V_pad = (V_ctc + 255) / 256 * 256;
+    void *w = nullptr, *b = nullptr;
+    HIP_TRY(ctx, hipMalloc(&w, (size_t)V_pad * d_enc * 2));
+    ctx->owned.push_back(w);
+    HIP_TRY(ctx, hipMalloc(&b, (size_t)V_pad * 4));
+    ctx->owned.push_back(b);
+    launch_ctc_head_pack(static_cast<const uint16_t*>(w_ctc), bias, V_ctc, V_pad, d_enc, static_cast<uint16_t*>(w),
+                         static_cast<float*>(b), ctx->stream);
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));     // the caller may release its copies on return
+    ctx->head_w = static_cast<uint16_t*>(w);
+    ctx->head_bias = static_cast<float*>(b);
+    ctx->head_V = V_ctc; ctx->head_V_pad = V_pad; ctx->head_d = d_enc;
+    return SSD_OK;
+}
+
+int ctc_head_gate(ssd_ctx* ctx, const void* enc_h, const int32_t* cu_frames, int B, int blank_id, float tau_ctc,
+                  float* frame_entropy, int32_t* frame_argmax, float* max_entropy, uint8_t* gate_pass,
+                  int32_t* draft_ctc, int32_t* draft_len) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->head_V) return fail(ctx, SSD_EINVAL, "ctc_head_gate: no output layer set (ssd_set_ctc_head)");
+    if (!enc_h || !cu_frames || !max_entropy || !gate_pass || !draft_ctc || !draft_len)
+        return fail(ctx, SSD_EINVAL, "ctc_head_gate: NULL argument");
+    if (B <= 0) return fail(ctx, SSD_EINVAL, "ctc_head_gate: B must be positive (got %d)", B);
+    const int V = ctx->head_V, d = ctx->head_d;
+    if (blank_id < 0 || blank_id >= V) return fail(ctx, SSD_EINVAL, "ctc_head_gate: blank_id %d outside [0, %d)", blank_id, V);
+    if (!check_cu(cu_frames, B, true))
+        return fail(ctx, SSD_EINVAL, "ctc_head_gate: cu_frames must start at 0 and increase strictly (every utterance needs a frame)");
+    const int64_t n_rows = cu_frames[B];
+    const HeadPlan p = plan_head(n_rows, B, V);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "ctc_head_gate: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+    char* ws = static_cast<char*>(ctx->ws);
+    float* H = frame_entropy ? frame_entropy : reinterpret_cast<float*>(ws + p.H);
+    int32_t* arg = frame_argmax ? frame_argmax : reinterpret_cast<int32_t*>(ws + p.arg);
+    int32_t* cu_dev = reinterpret_cast<int32_t*>(ws + p.cu);
+    int rc = upload(ctx, cu_frames, cu_dev, (size_t)(B + 1) * 4);
+    if (rc != SSD_OK) return rc;
+    {
+        ProfScope ps(ctx, SSD_PROF_CTC_HEAD);
+        // the kernels address the states with 32-bit byte offsets: at most 4 GiB of them per launch
+        const int64_t chunk = ((int64_t)0xffffffffu / ((int64_t)d * 2)) / 256 * 256;
+        for (int64_t r0 = 0; r0 < n_rows; r0 += chunk) {
+            const int rows = (int)std::min<int64_t>(chunk, n_rows - r0);
+            launch_ctc_head(static_cast<const uint16_t*>(enc_h) + r0 * d, ctx->head_w, ctx->head_bias, rows, d, V,
+                            ctx->head_V_pad, reinterpret_cast<float4*>(ws + p.part), H + r0, arg + r0, ctx->stream);
+        }
+        launch_gate_utterances(H, arg, cu_dev, B, blank_id, tau_ctc, max_entropy, gate_pass, draft_ctc, draft_len,
+                               ctx->stream);
     }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;

@@ -74,4 +74,24 @@ __device__ __forceinline__ int group_allreduce_i(int v, Op op) {
     return v;
 }
 
+// reduce over the 32 lanes of a half wavefront (same lane/32), e.g. the lanes that hold one row of
+// a 32x32 MFMA accumulator block
+template <class Op>
+__device__ __forceinline__ float row_allreduce32(float v, Op op) {
+    v = op(v, dpp_f<DPP_XOR1>(v));
+    v = op(v, dpp_f<DPP_XOR2>(v));
+    v = op(v, dpp_f<DPP_HALF_MIRROR>(v));
+    v = op(v, dpp_f<DPP_MIRROR>(v));
+    v = op(v, __shfl_xor(v, 16));
+    return v;
+}
+__device__ __forceinline__ int row_allmin32_i(int v) {
+    v = min(v, dpp_i<DPP_XOR1>(v));
+    v = min(v, dpp_i<DPP_XOR2>(v));
+    v = min(v, dpp_i<DPP_HALF_MIRROR>(v));
+    v = min(v, dpp_i<DPP_MIRROR>(v));
+    v = min(v, __shfl_xor(v, 16));
+    return v;
+}
+
 }  // namespace ssd

@@ -348,6 +348,13 @@ __global__ void __launch_bounds__(256) gate_utterances(const float* __restrict__
     }
 }
 
+void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int B, int blank,
+                            float tau, float* max_entropy, uint8_t* gate_pass, int32_t* draft, int32_t* draft_len,
+                            hipStream_t st) {
+    hipLaunchKernelGGL(gate_utterances, dim3(B), dim3(256), 0, st, H, arg, cu_frames_dev, blank, tau,
+                       max_entropy, gate_pass, draft, draft_len);
+}
+
 template <typename T, int LPR>
 static void launch_vec(const T* logits, int64_t n_rows, int V, float* H, int32_t* arg, hipStream_t st) {
     const int n_chunks = V / Chunk<T>::N;
@@ -394,8 +401,7 @@ void launch_gate(const void* logits, int dtype, int64_t n_rows, int V, const int
                  int32_t* draft, int32_t* draft_len, hipStream_t st) {
     if (dtype == SSD_BF16) launch_frames<bf16_t>(static_cast<const bf16_t*>(logits), n_rows, V, H, arg, st);
     else launch_frames<float>(static_cast<const float*>(logits), n_rows, V, H, arg, st);
-    hipLaunchKernelGGL(gate_utterances, dim3(B), dim3(256), 0, st, H, arg, cu_frames_dev, blank, tau,
-                       max_entropy, gate_pass, draft, draft_len);
+    launch_gate_utterances(H, arg, cu_frames_dev, B, blank, tau, max_entropy, gate_pass, draft, draft_len, st);
 }
 
 }  // namespace ssd

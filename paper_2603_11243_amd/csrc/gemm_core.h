@@ -28,6 +28,7 @@
 namespace ssd {
 
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void lds_void_t;
 
@@ -48,7 +49,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0xffffffff, 0x00020000);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE = 2>
+// BF16 = true: the operands are bfloat16 bit patterns and the bf16 MFMA is used (same shapes and rate).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE = 2, bool BF16 = false>
 struct GemmTile {
     static constexpr int WAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * WAVES;
@@ -121,7 +123,11 @@ struct GemmTile {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    if constexpr (BF16)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[i]),
+                                                                            __builtin_bit_cast(bf16x8_t, b[j]), acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         };
 
         // Software pipeline over n = kt1 - kt0 slices; slice i lives in stage i % NSTAGE.

@@ -15,17 +15,6 @@ constexpr int LM_WTN = 64;          // columns per group: every tile variant bel
 
 int lmhead_col_groups(int vocab) { return vocab / LM_WTN; }
 
-// reduce over the 32 lanes that share a row set (same lane/32)
-template <class Op>
-__device__ __forceinline__ float row_allreduce32(float v, Op op) {
-    v = op(v, dpp_f<DPP_XOR1>(v));
-    v = op(v, dpp_f<DPP_XOR2>(v));
-    v = op(v, dpp_f<DPP_HALF_MIRROR>(v));
-    v = op(v, dpp_f<DPP_MIRROR>(v));
-    v = op(v, __shfl_xor(v, 16));
-    return v;
-}
-
 template <int LM_BM, int LM_BN, int LM_WM, int LM_WN, int LM_NS, bool GREEDY>
 __global__ void __launch_bounds__(64 * LM_WM * LM_WN)
 lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,

@@ -15,6 +15,19 @@ void launch_gate(const void* logits, int dtype, int64_t n_rows, int V, const int
                  int blank, float tau, float* H, int32_t* arg, float* max_entropy, uint8_t* gate_pass,
                  int32_t* draft, int32_t* draft_len, hipStream_t st);
 
+// second half of the gate on its own: per-utterance max entropy, threshold test and collapse
+void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int B, int blank,
+                            float tau, float* max_entropy, uint8_t* gate_pass, int32_t* draft, int32_t* draft_len,
+                            hipStream_t st);
+
+// ---- ctc_head.hip: output layer of the CTC encoder fused with the frame statistics of the gate
+int ctc_head_groups(int V);      // column groups (of 64 symbols) that hold at least one real symbol
+void launch_ctc_head_pack(const uint16_t* w, const float* bias, int V, int V_pad, int d_enc, uint16_t* w_pad,
+                          float* bias_pad, hipStream_t st);
+// part: ctc_head_groups(V) * n_rows float4 of scratch; n_rows * d_enc * 2 bytes must stay below 4 GiB
+void launch_ctc_head(const uint16_t* enc_h, const uint16_t* w_pad, const float* bias_pad, int n_rows, int d_enc, int V,
+                     int V_pad, float4* part, float* H, int32_t* arg, hipStream_t st);
+
 // ---- row metadata built on the host for one verify_forward call
 // src code of a decoder row: speech rows hold the speech_emb row index; token rows hold
 // SRC_PROMPT | index into prompt_ids or SRC_DRAFT | index into draft_ids.
