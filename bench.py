@@ -162,6 +162,65 @@ def gate_roofline(ctx, wl, device):
             "frames": n_rows, "V_ctc": V, "storage": str(dt).replace("torch.", ""), "bytes_per_frame": V * z.element_size() + 12}
 
 
+def ctc_head_leg(ctx, wl, device, d_enc=1024, V=348):
+    """Output layer of the CTC encoder fused with the gate (1024-wide states, 348 symbols), next to
+    the same work done unfused: a library GEMM that stores bf16 scores, then ctc_gate on them.
+    About 0.8 GB of encoder states (400-frame utterances), HIP events through the library's profiler."""
+    if wl.model.dtype != "bf16":
+        return None
+    T = 400
+    n_utts = int(0.8e9 / (d_enc * 2)) // T
+    n_rows = n_utts * T
+    cu = np.arange(n_utts + 1, dtype=np.int32) * T
+    gen = torch.Generator(device=device)
+    gen.manual_seed(5)
+    w = (torch.randn(V, d_enc, device=device, generator=gen) / d_enc ** 0.5).bfloat16()
+    bias = 0.1 * torch.randn(V, device=device, generator=gen)
+    lab = torch.randint(0, V, (n_rows,), device=device, generator=gen)
+    h = torch.randn(n_rows, d_enc, device=device, generator=gen)
+    h += 8.0 * w.float()[lab] / (w.float()[lab] ** 2).sum(1, keepdim=True)
+    h = h.bfloat16()
+    del lab
+    blank = min(wl.blank_id, V - 1)
+    ctx.set_ctc_head(w, bias)
+    ctx.reserve(max_frames=n_rows, max_utts=n_utts)
+    ctx.ctc_head_gate(h, cu, blank, wl.tau_ctc)
+    torch.cuda.synchronize()
+    ctx.profile_select("ctc_head_gate")
+    for _ in range(10):
+        ctx.ctc_head_gate(h, cu, blank, wl.tau_ctc)
+    ms, n = ctx.profile_read()["ctc_head_gate"]
+    ctx.profile_select(-2)
+    fused_ms = ms / n
+    # unfused: scores through memory (library GEMM, padded to a 16-byte row for the gate kernel)
+    Vs = (V + 7) // 8 * 8
+    wp = torch.zeros(Vs, d_enc, device=device, dtype=torch.bfloat16)
+    wp[:V] = w
+    bp = torch.full((Vs,), -1e30, device=device)
+    bp[:V] = bias
+    z = torch.empty(n_rows, Vs, device=device, dtype=torch.bfloat16)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    def unfused():
+        torch.addmm(bp.bfloat16(), h, wp.t(), out=z)
+        return ctx.ctc_gate(z, cu, blank, wl.tau_ctc)
+    unfused()
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(10):
+        unfused()
+    ev[1].record()
+    torch.cuda.synchronize()
+    unfused_ms = ev[0].elapsed_time(ev[1]) / 10
+    flops = 2.0 * n_rows * d_enc * V
+    tf = flops / (fused_ms * 1e-3) / 1e12
+    return {"frames": n_rows, "d_enc": d_enc, "V_ctc": V, "ms_per_call": fused_ms, "frames_per_s": n_rows / (fused_ms * 1e-3),
+            "unfused_library_gemm_plus_gate_ms": unfused_ms, "speedup_vs_unfused": unfused_ms / fused_ms,
+            "roofline": {"bound": "mfma", "kernel": "ctc_head_partials_kernel (+ merge and per-utterance kernels)",
+                         "achieved": tf, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_TFLOPS,
+                         "flops_per_call": flops, "note": "348 symbols occupy 512 MFMA columns: 68 % of the issued flops are algorithmic"},
+            "bytes_per_frame": {"fused": d_enc * 2 + 16 * ((V + 63) // 64) * 2 + 12, "unfused": d_enc * 2 + 2 * Vs * 2 + 12}}
+
+
 def ar_fallback_leg(ctx, wl, meta, tau, n_steps=16):
     """Eq. 6 after the timed path: verify with the K/V cache, accept with greedy tokens, then n_steps of
     greedy continuation for the utterances whose draft was not fully accepted.  A decode step streams
@@ -297,6 +356,7 @@ def main():
     out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
     out["ar_fallback"] = ar_fallback_leg(ctx, wl, meta, tau)
     out["gate_roofline"] = gate_roofline(ctx, wl, device)
+    out["ctc_head_gate"] = ctc_head_leg(ctx, wl, device)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)
     print(json.dumps(out))

@@ -141,7 +141,7 @@ int ctc_gate(ssd_ctx *ctx, const void *logits, int dtype, const int32_t *cu_fram
              int32_t *draft_ctc /*dev [cu_frames[B]]*/, int32_t *draft_len /*dev [B]*/);
 
 /* Sec. 3.1 (output layer of the CTC encoder: 1024-wide states, 348 symbols) feeding Sec. 2.1.
- * ssd_set_ctc_head copies the output layer into the context (zero-padded to a multiple of 256
+ * ssd_set_ctc_head copies the output layer into the context (padded to a multiple of 128
  * symbols; the caller's arrays may be released on return; a second call replaces the first).
  * w_ctc: dev [V_ctc, d_enc] bfloat16 row-major; bias: dev [V_ctc] fp32 or NULL (zero);
  * d_enc a multiple of 64, V_ctc <= 65536.  Allocates device memory; waits for the stream.

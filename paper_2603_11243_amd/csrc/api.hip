@@ -92,7 +92,7 @@ struct ssd_ctx {
     float* rope_tab = nullptr;               // [max_positions][head_dim/2] (cos, sin) pairs
     void* ws = nullptr;
     size_t ws_bytes = 0;
-    uint16_t* head_w = nullptr;              // CTC output layer, rows padded with zeros to a multiple of 256
+    uint16_t* head_w = nullptr;              // CTC output layer, padded with zero rows (bias -inf there)
     float* head_bias = nullptr;
     int head_V = 0, head_V_pad = 0, head_d = 0;
     void* kv = nullptr;                      // caller-owned K/V cache: [layer][K|V][slots][d_kv] in the activation type
@@ -556,7 +556,7 @@ int ssd_set_ctc_head(ssd_ctx* ctx, const void* w_ctc, const float* bias, int V_c
     };
     drop(ctx->head_w); drop(ctx->head_bias);
     ctx->head_w = nullptr; ctx->head_bias = nullptr; ctx->head_V = 0;
-    const int V_pad = (V_ctc + 255) / 256 * 256;
+    const int V_pad = ctc_head_padded(V_ctc);
     void *w = nullptr, *b = nullptr;
     HIP_TRY(ctx, hipMalloc(&w, (size_t)V_pad * d_enc * 2));
     ctx->owned.push_back(w);

@@ -3,81 +3,93 @@
 // The encoder's output layer (Sec. 3.1: 1024-wide states, 348 CTC symbols) produces the scores that
 // Eq. 2 (greedy symbol per frame) and Eq. 3 (frame entropy) consume.  Here the scores
 //     z[t, v] = enc_h[t] . W[v] + b[v]
-// only ever exist in MFMA accumulators: every wavefront reduces its [rows x 64 columns] slab to
+// only ever exist in MFMA accumulators.  The product is formed transposed, Z^T = W . enc_h^T, so that
+// an accumulator lane owns one frame (its column) and 16 symbols per 32x32 block (its registers):
+// the per-frame reductions over symbols run inside the lane, with a single exchange between the two
+// lane halves at the end.  Every wavefront reduces its [64 symbols x frames] slab to
 //     m = max_v z,  arg = lowest v with z = m,  S = sum_v e^(z-m),  W = sum_v e^(z-m) (z-m)
-// per row (16 bytes), and a second small kernel merges the column groups of a row into
+// per frame (16 bytes), and a second small kernel merges the symbol groups of a frame into
 //     H_t = log S - W / S   ( = -sum_v p log p for p = softmax(z) ),   argmax_t.
 // Written per frame: 16 bytes per group of 64 symbols instead of 2 x 2 bytes per symbol (a store of
 // bf16 scores and the gate's load of them).  Operands are the stored bf16 values (bf16 MFMA, exact
-// products, fp32 accumulation).
+// products, fp32 accumulation); the accumulators start at the bias, and symbols added as padding
+// have zero weights and bias -inf, i.e. probability zero.
 #include "gemm_core.h"
 #include "ssd_internal.h"
 
 namespace ssd {
 
-constexpr int CH_WTN = 64;          // symbols per column group
+constexpr int CH_BM = 128;          // symbols per tile
+constexpr int CH_GROUP = 64;        // symbols per partial: the wave tile height of every variant below
+constexpr int CH_PAD = 128;         // symbol count is padded to a multiple of this
 
-template <int BM, int BN, int WM, int WN, int NS>
+template <int BN, int WM, int WN, int NS>
 __global__ void __launch_bounds__(64 * WM * WN)
 ctc_head_partials_kernel(const uint16_t* __restrict__ enc_h, const uint16_t* __restrict__ w_pad,
-                         const float* __restrict__ bias_pad, int n_rows, int d_enc, int V, int tiles_m,
+                         const float* __restrict__ bias_pad, int n_rows, int d_enc, int V, int V_pad,
                          float4* __restrict__ part) {
-    using Tile = GemmTile<BM, BN, WM, WN, NS, true>;
-    static_assert(Tile::WTN == CH_WTN, "column groups are 64 wide");
+    using Tile = GemmTile<CH_BM, BN, WM, WN, NS, true>;
+    static_assert(Tile::WTM == CH_GROUP, "one partial per wave tile of 64 symbols");
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    // row tiles vary fastest: workgroups that run together share one slab of the (small) weight
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    // symbol tiles vary fastest, and the tiles of one slab of frames run on one XCD (one fetch of the slab)
+    const int tiles_v = V_pad / CH_BM;
+    const int v = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const int tv = v % tiles_v, tf = v / tiles_v;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / WN, wn = wave % WN;
+    const int sym0 = tv * CH_BM + wm * Tile::WTM;            // first symbol of this wavefront
+    const int frame0 = tf * BN + wn * Tile::WTN;
+    const int half = lane / 32;
+
     f32x16_t acc[Tile::TM][Tile::TN];
 #pragma unroll
     for (int i = 0; i < Tile::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < Tile::TN; ++j)
+        for (int q = 0; q < 4; ++q) {
+            const float4 b4 = *reinterpret_cast<const float4*>(bias_pad + sym0 + i * 32 + 8 * q + 4 * half);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile::run(reinterpret_cast<const f16_t*>(enc_h), reinterpret_cast<const f16_t*>(w_pad), n_rows, d_enc, tm * BM,
-              tn * BN, 0, d_enc / GEMM_BK, smem_raw, acc);
+            for (int j = 0; j < Tile::TN; ++j) {
+                acc[i][j][4 * q + 0] = b4.x; acc[i][j][4 * q + 1] = b4.y;
+                acc[i][j][4 * q + 2] = b4.z; acc[i][j][4 * q + 3] = b4.w;
+            }
+        }
+    Tile::run(reinterpret_cast<const f16_t*>(w_pad), reinterpret_cast<const f16_t*>(enc_h), V_pad, d_enc, tv * CH_BM,
+              tf * BN, 0, d_enc / GEMM_BK, smem_raw, acc, n_rows);
 
-    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const int wm = wave / WN, wn = wave % WN;
-    const int row0 = tm * BM + wm * Tile::WTM, col0 = tn * BN + wn * Tile::WTN;
-    if (col0 >= V) return;                               // group made of padding columns only
-    const int group = col0 / CH_WTN;
-    float bias[Tile::TN];
-    bool valid[Tile::TN];
+    if (sym0 >= V) return;                                   // slab made of padding symbols only
+    const int group = sym0 / CH_GROUP;
+    constexpr float LOG2E = 1.4426950408889634f;
 #pragma unroll
     for (int j = 0; j < Tile::TN; ++j) {
-        const int c = col0 + acc_col(j, lane);
-        valid[j] = c < V;
-        bias[j] = bias_pad[c];
-    }
+        const int frame = frame0 + j * 32 + lane % 32;
+        float m = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < Tile::TM; ++i)
+        for (int i = 0; i < Tile::TM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = row0 + acc_row(i, r, lane);
-            float z[Tile::TN];
-            float mx = -INFINITY;
-            int best_c = 0x7fffffff;
+            for (int r = 0; r < 16; r += 2) m = fmaxf(m, fmaxf(acc[i][j][r], acc[i][j][r + 1]));
+        m = fmaxf(m, __shfl_xor(m, 32));                     // finite: symbol sym0 is real
+        const float mL = m * LOG2E;
+        float s = 0.f, w = 0.f;
+        int rel = 0x7fffffff;                                // symbol index relative to sym0 + 4*half
+        // descending symbol order: the last match is the lowest index
 #pragma unroll
-            for (int j = 0; j < Tile::TN; ++j) {
-                z[j] = valid[j] ? acc[i][j][r] + bias[j] : -INFINITY;
-                if (z[j] > mx) { mx = z[j]; best_c = col0 + acc_col(j, lane); }
-            }
-            const float m = row_allreduce32(mx, OpMax());      // finite: column col0 is valid
-            const int arg = row_allmin32_i(mx == m ? best_c : 0x7fffffff);
-            float s = 0.f, w = 0.f;
+        for (int i = Tile::TM - 1; i >= 0; --i)
 #pragma unroll
-            for (int j = 0; j < Tile::TN; ++j) {
-                const float t = z[j] - m;
-                const float e = __expf(t);
+            for (int r = 15; r >= 0; --r) {
+                const float z = acc[i][j][r];
+                const float t2 = fmaf(z, LOG2E, -mL);        // (z - m) log2 e  <= 0; -inf for padding
+                const float e = __builtin_amdgcn_exp2f(t2);
                 s += e;
-                w += valid[j] ? e * t : 0.f;
+                w = fmaf(e, fmaxf(t2, -200.f), w);           // e is 0 there; keeps 0 * inf out
+                if (z == m) rel = i * 32 + 8 * (r / 4) + (r % 4);
             }
-            s = row_allreduce32(s, OpSum());
-            w = row_allreduce32(w, OpSum());
-            if (row < n_rows && lane % 32 == 0)
-                part[(int64_t)group * n_rows + row] = make_float4(m, s, w, __int_as_float(arg));
-        }
+        int arg = rel == 0x7fffffff ? rel : sym0 + 4 * half + rel;
+        s += __shfl_xor(s, 32);
+        w += __shfl_xor(w, 32);
+        arg = min(arg, __shfl_xor(arg, 32));
+        if (frame < n_rows && half == 0)
+            part[(int64_t)group * n_rows + frame] = make_float4(m, s, w * (1.0f / LOG2E), __int_as_float(arg));
+    }
 }
 
 // One thread per frame merges its column groups (coalesced: group-major partials).
@@ -102,43 +114,42 @@ __global__ void __launch_bounds__(256) ctc_head_finalize_kernel(const float4* __
     arg[row] = best;
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
+template <int BN, int WM, int WN, int NS>
 static void launch_partials(const uint16_t* enc_h, const uint16_t* w_pad, const float* bias_pad, int n_rows, int d_enc,
                             int V, int V_pad, float4* part, hipStream_t st) {
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, NS>();
-    auto kern = ctc_head_partials_kernel<BM, BN, WM, WN, NS>;
+    constexpr size_t lds = gemm_lds_bytes<CH_BM, BN, NS>();
+    auto kern = ctc_head_partials_kernel<BN, WM, WN, NS>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    const int tiles_m = (n_rows + BM - 1) / BM;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * (V_pad / BN)), dim3(64 * WM * WN), lds, st, enc_h, w_pad, bias_pad, n_rows,
-                       d_enc, V, tiles_m, part);
+    const int tiles_f = (n_rows + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_f * (V_pad / CH_BM)), dim3(64 * WM * WN), lds, st, enc_h, w_pad, bias_pad,
+                       n_rows, d_enc, V, V_pad, part);
 }
 
-int ctc_head_groups(int V) { return (V + CH_WTN - 1) / CH_WTN; }
+int ctc_head_groups(int V) { return (V + CH_GROUP - 1) / CH_GROUP; }
+int ctc_head_padded(int V) { return (V + CH_PAD - 1) / CH_PAD * CH_PAD; }
 
-// enc_h [n_rows, d_enc] bf16; w_pad [V_pad, d_enc] bf16 with zero rows beyond V; bias_pad [V_pad] fp32;
-// part: ctc_head_groups(V) * n_rows float4.  n_rows * d_enc * 2 must stay below 4 GiB (32-bit offsets).
+// enc_h [n_rows, d_enc] bf16; w_pad [V_pad, d_enc] bf16 with zero rows beyond V; bias_pad [V_pad] fp32, -inf
+// beyond V; part: ctc_head_groups(V) * n_rows float4.  n_rows * d_enc * 2 must stay below 4 GiB.
 void launch_ctc_head(const uint16_t* enc_h, const uint16_t* w_pad, const float* bias_pad, int n_rows, int d_enc, int V,
                      int V_pad, float4* part, float* H, int32_t* arg, hipStream_t st) {
     if (n_rows <= 0) return;
-    // fewer than one 256-row tile per compute unit and column slab: halve the tile height (three LDS stages)
-    if ((n_rows + 255) / 256 < 256) launch_partials<128, 256, 2, 4, 3>(enc_h, w_pad, bias_pad, n_rows, d_enc, V, V_pad, part, st);
-    else launch_partials<256, 256, 2, 4, 2>(enc_h, w_pad, bias_pad, n_rows, d_enc, V, V_pad, part, st);
+    launch_partials<256, 2, 4, 3>(enc_h, w_pad, bias_pad, n_rows, d_enc, V, V_pad, part, st);
     hipLaunchKernelGGL(ctc_head_finalize_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, part, ctc_head_groups(V),
                        n_rows, H, arg);
 }
 
-// zero-padded copy of the output layer: rows [V, V_pad) are zero, bias there is zero too (masked by column index)
+// padded copy of the output layer: rows [V, V_pad) are zero and their bias is -inf
 __global__ void ctc_head_pack_kernel(const uint16_t* __restrict__ w, const float* __restrict__ bias, int V, int V_pad,
                                      int d_enc, uint16_t* __restrict__ w_pad, float* __restrict__ bias_pad) {
     const int64_t n = (int64_t)V_pad * d_enc;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
         w_pad[i] = (i / d_enc < V) ? w[i] : (uint16_t)0;
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < V_pad) bias_pad[c] = (c < V && bias) ? bias[c] : 0.f;
+    if (c < V_pad) bias_pad[c] = c < V ? (bias ? bias[c] : 0.f) : -INFINITY;
 }
 
 void launch_ctc_head_pack(const uint16_t* w, const float* bias, int V, int V_pad, int d_enc, uint16_t* w_pad,

@@ -19,7 +19,7 @@
 // (consecutive rows, same logical chunk) then spreads every 16 lanes over all sixteen 16-byte
 // columns of the 256-byte LDS data path (measured: SQ_LDS_BANK_CONFLICT drops to zero; with
 // c ^ (r & 7) half of the LDS cycles were conflict cycles).
-// Rows >= M are clamped on load and must be skipped by the epilogue.
+// Rows >= M (and columns >= n_rows_w, if given) are clamped on load and must be skipped by the epilogue.
 // Requirements: N % BN == 0, K % 64 == 0, A and W 16-byte aligned and smaller than 4 GiB.
 #pragma once
 #include <type_traits>
@@ -34,6 +34,16 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 
 constexpr int GEMM_BK = 64;
 constexpr int GEMM_ROW_BYTES = GEMM_BK * 2;
+
+// Hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each with its own L2.  This maps
+// a workgroup id to a work index such that every XCD walks one contiguous run of indices, so that
+// neighbouring indices (which share operand panels) meet in the same L2.
+__device__ __forceinline__ int xcd_contiguous_index(int pid, int total) {
+    constexpr int XCDS = 8;
+    const int per = total / XCDS, rem = total % XCDS;
+    const int xcd = pid % XCDS, idx = pid / XCDS;
+    return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+}
 
 template <int BM, int BN, int NSTAGE = 2>
 constexpr size_t gemm_lds_bytes() { return (size_t)NSTAGE * (BM + BN) * GEMM_ROW_BYTES; }
@@ -63,11 +73,12 @@ struct GemmTile {
     static_assert(BM % (8 * WAVES) == 0 && BN % (8 * WAVES) == 0, "tile/thread mismatch");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
 
-    // acc must be zero-initialised by the caller.  smem: gemm_lds_bytes<BM,BN,NSTAGE>() bytes, 16-byte
+    // acc is accumulated onto (zero it for a plain product).  Rows of W at and beyond n_rows_w are
+    // clamped on load like the rows of A beyond M (for callers whose ragged dimension is N).  smem: gemm_lds_bytes<BM,BN,NSTAGE>() bytes, 16-byte
     // aligned.  Slices kt0 <= kt < kt1 of K are accumulated (K itself is the row stride of A and W).
     static __device__ __forceinline__ void run(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int K,
                                                int m0, int n0, int kt0, int kt1, unsigned char* smem,
-                                               f32x16_t (&acc)[TM][TN]) {
+                                               f32x16_t (&acc)[TM][TN], int n_rows_w = 0x7fffffff) {
         const int tid = threadIdx.x, lane = tid % 64;
         const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
         const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -86,7 +97,7 @@ struct GemmTile {
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
             const int r = (i * WAVES + wave) * 8 + lrow;
-            b_off[i] = (unsigned)(n0 + r) * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
+            b_off[i] = (unsigned)min(n0 + r, n_rows_w - 1) * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
         }
         auto issue_loads = [&](int kt, int stage) {
             unsigned char* sa = smem + stage * STAGE_BYTES;

@@ -13,14 +13,11 @@
 
 namespace ssd {
 
-// Workgroup id -> tile.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each
-// with its own L2; ids are first regrouped so that one XCD walks a contiguous run of tiles, and
-// tiles are ordered in bands of GROUP_M row-tiles so that the run reuses few A and W panels.
+// Workgroup id -> tile: one XCD walks a contiguous run of tiles, and tiles are ordered in bands of
+// GROUP_M row-tiles so that the run reuses few A and W panels.
 __device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_m, int tiles_n, int& tm, int& tn) {
-    constexpr int XCDS = 8, GROUP_M = 4;
-    const int per = total / XCDS, rem = total % XCDS;
-    const int xcd = pid % XCDS, idx = pid / XCDS;
-    const int v = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    constexpr int GROUP_M = 4;
+    const int v = xcd_contiguous_index(pid, total);
     const int band = v / (GROUP_M * tiles_n);
     const int first_m = band * GROUP_M;
     const int rows = min(tiles_m - first_m, GROUP_M);

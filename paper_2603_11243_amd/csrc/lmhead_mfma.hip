@@ -24,8 +24,9 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
     static_assert(Tile::WTN == LM_WTN, "column groups are 64 wide");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (Mv + LM_BM - 1) / LM_BM;
-    // row tiles vary fastest: workgroups that run together share one slab of W_lm
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    // row tiles vary fastest, and the row tiles of one slab of W_lm run on one XCD (one fetch of the slab)
+    const int v = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const int tm = v % tiles_m, tn = v / tiles_m;
     f32x16_t acc[Tile::TM][Tile::TN];
 #pragma unroll
     for (int i = 0; i < Tile::TM; ++i)

@@ -21,7 +21,8 @@ void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* c
                             hipStream_t st);
 
 // ---- ctc_head.hip: output layer of the CTC encoder fused with the frame statistics of the gate
-int ctc_head_groups(int V);      // column groups (of 64 symbols) that hold at least one real symbol
+int ctc_head_groups(int V);      // groups of 64 symbols that hold at least one real symbol
+int ctc_head_padded(int V);      // symbol count after padding
 void launch_ctc_head_pack(const uint16_t* w, const float* bias, int V, int V_pad, int d_enc, uint16_t* w_pad,
                           float* bias_pad, hipStream_t st);
 // part: ctc_head_groups(V) * n_rows float4 of scratch; n_rows * d_enc * 2 bytes must stay below 4 GiB
