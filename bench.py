@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # plain 1 GiB device copy (`--copy-reference`): FETCH_SIZE reads 524300 for 1048576 KiB (factor 2.0),
 # WRITE_SIZE reads 1048576 (factor 1.0).  See profiles/pmc_traffic_gemm_gate_up_cfg3.md.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_1b_ragged64": (340791.9 * 2.0 + 82304.0 * 1.0) * 1024.0,
+    "cfg3_1b_ragged64": (331325.6 * 2.0 + 82304.0 * 1.0) * 1024.0,
 }
 
 
@@ -265,6 +265,8 @@ def main():
     ap.add_argument("--workload", default="cfg3_1b_ragged64", choices=list(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-tokens", type=int, default=3000)
+    ap.add_argument("--main-only", action="store_true",
+                    help="skip the side legs (MFMA ceiling, AR fallback, gate saturation, CTC head): for counter runs")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (scale reference for --pmc counters)")
     args = ap.parse_args()
@@ -350,13 +352,14 @@ def main():
         "all_projection_gemms": {"tflops": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
                                  "frac_of_peak": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
     }
-    tf, ghz = ctx.measure_mfma_ceiling(20000)
-    out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
-                                       "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
-    out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
-    out["ar_fallback"] = ar_fallback_leg(ctx, wl, meta, tau)
-    out["gate_roofline"] = gate_roofline(ctx, wl, device)
-    out["ctc_head_gate"] = ctc_head_leg(ctx, wl, device)
+    if not args.main_only:
+        tf, ghz = ctx.measure_mfma_ceiling(20000)
+        out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
+                                           "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
+        out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
+        out["ar_fallback"] = ar_fallback_leg(ctx, wl, meta, tau)
+        out["gate_roofline"] = gate_roofline(ctx, wl, device)
+        out["ctc_head_gate"] = ctc_head_leg(ctx, wl, device)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)
     print(json.dumps(out))
