@@ -129,11 +129,95 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
     }
 }
 
+// head_dim 128 in half precision: lane = (key group kg of 4, chunk dc of 8 dims).  A block of 64 keys
+// is 16 loads of K and 16 of V per lane, all issued before the first use (the rows are 256 bytes, a
+// 16-lane group reads one row); a score is a 16-lane reduction, the softmax statistics are reduced over
+// the four key groups, and P.V accumulates in the lane (no LDS), reduced over the key groups at the end.
+__global__ void __launch_bounds__(64) decode_attn_hd128_kernel(const f16_t* __restrict__ qkv, const f16_t* __restrict__ kc,
+                                                               const f16_t* __restrict__ vc, const int32_t* __restrict__ kv_start,
+                                                               const int32_t* __restrict__ n_ctx, int n_q_heads, int n_kv_heads,
+                                                               f16_t* __restrict__ out) {
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    constexpr int HD = 128;
+    const int lane = threadIdx.x, kg = lane / 16, dc = lane % 16;
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int kvh = h / (n_q_heads / n_kv_heads);
+    const int d_q = n_q_heads * HD, d_kv = n_kv_heads * HD;
+    float qf[8];
+    load8(qkv + (int64_t)b * (d_q + 2 * d_kv) + h * HD + dc * 8, qf);
+    const float sc = 0.08838834764831845f * 1.4426950408889634f;      // log2(e) / sqrt(128)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[e] *= sc;
+    const int n = n_ctx[b];
+    const f16_t* kbase = kc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
+    const f16_t* vbase = vc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
+    float m = -INFINITY, l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < n; k0 += 64) {
+        uint4 kr[16], vr[16];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int key = min(k0 + it * 4 + kg, n - 1);
+            kr[it] = *reinterpret_cast<const uint4*>(kbase + (int64_t)key * d_kv);
+        }
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int key = min(k0 + it * 4 + kg, n - 1);
+            vr[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)key * d_kv);
+        }
+        float s[16];
+        float cm = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const h8 kk = __builtin_bit_cast(h8, kr[it]);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(qf[e], (float)kk[e], acc);
+            acc = group_allreduce<16>(acc, OpSum());
+            s[it] = (k0 + it * 4 + kg < n) ? acc : -INFINITY;
+            cm = fmaxf(cm, s[it]);
+        }
+        cm = fmaxf(cm, __shfl_xor(cm, 16));
+        cm = fmaxf(cm, __shfl_xor(cm, 32));
+        const float m_new = fmaxf(m, cm);                 // finite: key k0 exists
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= alpha;
+        float ps = 0.f;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const float p = __builtin_amdgcn_exp2f(s[it] - m_new);
+            ps += p;
+            const h8 vv = __builtin_bit_cast(h8, vr[it]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(p, (float)vv[e], o[e]);
+        }
+        ps += __shfl_xor(ps, 16);
+        ps += __shfl_xor(ps, 32);
+        l = l * alpha + ps;
+        m = m_new;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        o[e] += __shfl_xor(o[e], 16);
+        o[e] += __shfl_xor(o[e], 32);
+    }
+    if (kg == 0) {
+        const float inv = 1.0f / l;
+        uint4 w;
+        w.x = pack_f16x2(o[0] * inv, o[1] * inv); w.y = pack_f16x2(o[2] * inv, o[3] * inv);
+        w.z = pack_f16x2(o[4] * inv, o[5] * inv); w.w = pack_f16x2(o[6] * inv, o[7] * inv);
+        *reinterpret_cast<uint4*>(out + (int64_t)b * d_q + h * HD + dc * 8) = w;
+    }
+}
+
 void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
                         const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
                         hipStream_t st) {
     if (Br <= 0) return;
-    if (dtype == SSD_BF16)
+    if (dtype == SSD_BF16 && head_dim == 128)
+        hipLaunchKernelGGL(decode_attn_hd128_kernel, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out);
+    else if (dtype == SSD_BF16)
         hipLaunchKernelGGL(decode_attn_kernel<f16_t>, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
                            (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (f16_t*)out);
     else

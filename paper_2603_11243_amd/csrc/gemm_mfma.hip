@@ -174,11 +174,19 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
 // Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
 // of 256 for every GEMM here); the tile height is picked per launch so that the number of tiles
 // wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
-// With at most 128 rows the job is weight streaming: a skinny 128 x 64 tile (four wavefronts, each
-// 32 rows x 64 columns) with a four-stage LDS ring gives N/64 workgroups with 72 KB in flight each.
+// With at most 128 rows the job is weight streaming and what counts is the number of weight bytes in
+// flight: a skinny 128 x 64 tile (four wavefronts, each 32 rows x 64 columns) with a six-stage LDS ring
+// (144 KB, five slices in flight), and for at most 32 rows a 32 x 64 tile of one wavefront, six stages
+// of 12 KB, two workgroups per CU.
+template <class Epi>
+static void launch_skinny(const f16_t* A, const f16_t* W, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
+    if (M <= 32) launch_gemm<32, 64, 1, 1, 6>(A, W, M, N, K, splits, epi, st);
+    else launch_gemm<128, 64, 4, 1, 6>(A, W, M, N, K, splits, epi, st);
+}
+
 template <class Epi>
 static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
-    if (M <= SKINNY_MAX_ROWS) { launch_gemm<128, 64, 4, 1, 4>(A, W, M, N, K, 1, epi, st); return; }
+    if (M <= SKINNY_MAX_ROWS) { launch_skinny(A, W, M, N, K, 1, epi, st); return; }
     const int heights[3] = {256, 192, 128};
     const double eff[3] = {1.0, 0.97, 0.90};
     int best = 0;
@@ -216,7 +224,7 @@ int launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, float* 
     const int splits = gemm_residual_splits(M, N, K);
     if (splits > 1) {
         EpiPartial epi{partials, N, (int64_t)M * N, descale};
-        launch_gemm<128, 64, 4, 1, 4>(A, W, M, N, K, splits, epi, st);
+        launch_skinny(A, W, M, N, K, splits, epi, st);
         return splits;
     }
     EpiResidual epi{x, N, descale};
