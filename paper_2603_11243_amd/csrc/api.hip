@@ -380,6 +380,9 @@ size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_t
     if (ctx->head_V) need = std::max(need, plan_head(max_frames, max_utts, ctx->head_V).total);
     if (ctx->has_model) {
         need = std::max(need, plan_verify(ctx->cfg, max_tokens, max_verify_rows, max_utts).total);
+        // a smaller batch may take the few-row path, which needs split-K scratch the big plan does not have
+        const int64_t few = std::min<int64_t>(max_tokens, SKINNY_MAX_ROWS);
+        need = std::max(need, plan_verify(ctx->cfg, few, std::min(max_verify_rows, few), std::min(max_utts, few)).total);
         need = std::max(need, plan_accept(ctx->cfg, max_verify_rows, max_utts).total);
     }
     return need + 256;
