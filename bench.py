@@ -34,11 +34,6 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def layer_gemm_flops(m, M):
-    """2 * M * (parameters of the projection matrices of one layer)."""
-    return 2.0 * M * m.params_per_layer()
-
-
 class Step:
     """Everything one step needs, prepared once; `run()` enqueues one step and returns its outputs."""
 
@@ -322,10 +317,17 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     M = int(meta["cu_s"][-1] + meta["cu_p"][-1] + meta["cu_d"][-1])
     Bv = len(meta["fail"])
-    gate_up_flops = 2.0 * M * m.d_model * 2 * m.d_ff
+    # rows per launch: M in every layer but the last, where only the Mv verification rows continue after
+    # attention (Eq. 5 scores nothing else); the average launch is priced with the average row count
+    Mv = int(meta["cu_d"][-1])
+    L = m.n_layers
+    rows_avg = ((L - 1) * M + Mv) / L
+    gate_up_flops = 2.0 * rows_avg * m.d_model * 2 * m.d_ff
     avg_ms = dom_ms / max(dom_n, 1)
     achieved = gate_up_flops / (avg_ms * 1e-3) / 1e12 if dom_n else 0.0
     gemm_ms = sum(breakdown[k] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down"))
+    qkv_params = m.d_model * (m.d_q + 2 * m.d_kv)
+    step_gemm_flops = 2.0 * (L * M * qkv_params + L * rows_avg * (m.params_per_layer() - qkv_params))
     acc_len = acc["accept_len"].cpu().numpy()
     out = {
         "metric": "verified draft tokens/s (gate+verify+accept, whole step)",
@@ -346,11 +348,12 @@ def main():
                      "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_MFMA_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "traffic_unit": "bytes per launch (L2<->fabric, incl. Infinity Cache hits)",
-                     "algorithmic_bytes": 2.0 * (M * m.d_model + 2 * m.d_ff * m.d_model + M * m.d_ff),
+                     "algorithmic_bytes": 2.0 * (rows_avg * m.d_model + 2 * m.d_ff * m.d_model + rows_avg * m.d_ff),
+                     "rows_per_launch": {"layers_before_last": M, "last_layer": Mv, "average": rows_avg},
                      "avg_launch_ms": avg_ms, "launches_timed": dom_n, "flops_per_launch": gate_up_flops},
         "breakdown_ms_per_step": breakdown,
-        "all_projection_gemms": {"tflops": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
-                                 "frac_of_peak": m.n_layers * layer_gemm_flops(m, M) / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
+        "all_projection_gemms": {"tflops": step_gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
+                                 "frac_of_peak": step_gemm_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
     }
     if not args.main_only:
         tf, ghz = ctx.measure_mfma_ceiling(20000)

@@ -182,8 +182,11 @@ int attn_tile_rows(int dtype) { return dtype == SSD_BF16 ? 64 : 4; }
 
 struct VerifyPlan {
     size_t row_src, pos, vrow, row_slot, tiles, meta_bytes;     // metadata block, uploaded in one copy
-    size_t x, a, qkv, attn, gu, h, partials, total;   // activations
+    size_t x, a, qkv, attn, gu, h, x_c, attn_c, partials, total;   // activations
 };
+// rows that may go through the few-row GEMM path (split-K scratch): the whole batch, or the
+// verification rows of the last layer
+int64_t skinny_rows(int64_t M, int64_t Mv) { return M <= SKINNY_MAX_ROWS ? M : (Mv <= SKINNY_MAX_ROWS ? Mv : 0); }
 VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t utts) {
     VerifyPlan p;
     const size_t es = elem_size(c.dtype);
@@ -202,8 +205,11 @@ VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t ut
     p.attn = o; o = align_up(o + (size_t)(M * dq) * es);
     p.gu = o; if (c.dtype == SSD_F32) o = align_up(o + (size_t)(M * 2 * c.d_ff) * 4);
     p.h = o; o = align_up(o + (size_t)(M * c.d_ff) * es);
+    // last layer: only the verification rows go on after attention
+    p.x_c = o; if (c.dtype == SSD_BF16) o = align_up(o + (size_t)(Mv * d) * 4);
+    p.attn_c = o; if (c.dtype == SSD_BF16) o = align_up(o + (size_t)(Mv * dq) * es);
     p.partials = o;
-    if (c.dtype == SSD_BF16 && M <= SKINNY_MAX_ROWS) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * M * d * 4);
+    if (c.dtype == SSD_BF16) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * skinny_rows(M, Mv) * d * 4);
     p.total = o;
     return p;
 }
@@ -383,6 +389,7 @@ size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_t
         // a smaller batch may take the few-row path, which needs split-K scratch the big plan does not have
         const int64_t few = std::min<int64_t>(max_tokens, SKINNY_MAX_ROWS);
         need = std::max(need, plan_verify(ctx->cfg, few, std::min(max_verify_rows, few), std::min(max_utts, few)).total);
+        need = std::max(need, plan_verify(ctx->cfg, max_tokens, std::min<int64_t>(max_verify_rows, SKINNY_MAX_ROWS), max_utts).total);
         need = std::max(need, plan_accept(ctx->cfg, max_verify_rows, max_utts).total);
     }
     return need + 256;
@@ -695,6 +702,13 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     float* partials = reinterpret_cast<float*>(ws + p.partials);
     const int64_t split_stride = (int64_t)Mi * d;
     int pending = 1;            // K splits of the last residual projection still to be added to x (1: none)
+    // Rows that continue after the attention of the last layer: Eq. 5 needs the output distribution at
+    // the verification positions only, so the output projection and the MLP of that layer run on those
+    // Mv rows (gathered), not on all M.  Exactly the same values: rows do not interact after attention.
+    float* x_c = reinterpret_cast<float*>(ws + p.x_c);
+    void* att_c = ws + p.attn_c;
+    const int Mvi = (int)Mv;
+    bool compact = false;
     for (int l = 0; l < m.n_layers; ++l) {
         { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
         pending = 1;
@@ -702,11 +716,19 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st); }
             if (kv_start) { ProfScope ps(ctx, SSD_PROF_OTHER); launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Mi, d, dq, ctx->ds_o[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
+            float* xr = x; const void* attr = att; int rows = Mi;
+            if (l == m.n_layers - 1) {
+                ProfScope ps(ctx, SSD_PROF_OTHER);
+                launch_gather_rows(att, d_vrow, Mvi, (int64_t)dq * 2, att_c, st);
+                launch_gather_rows(x, d_vrow, Mvi, (int64_t)d * 4, x_c, st);
+                xr = x_c; attr = att_c; rows = Mvi; compact = true;
+            }
+            const int64_t stride = (int64_t)rows * d;
+            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], xr, partials, rows, d, dq, ctx->ds_o[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, st); }
             pending = 1;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Mi, m.d_ff, d, ctx->ds_gu[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, partials, Mi, d, m.d_ff, ctx->ds_down[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
@@ -720,8 +742,14 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
             launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Mi, d, m.d_ff, F32_ADD, st);
         }
     }
-    // verification rows only: final RMSNorm of the positions that score a draft token
-    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, (int)Mv, d, m.rms_eps, h_verify, partials, pending, split_stride, st); }
+    // final RMSNorm of the positions that score a draft token
+    if (compact) {
+        ProfScope ps(ctx, SSD_PROF_OTHER);
+        launch_rmsnorm(m.dtype, x_c, ctx->norm_final, nullptr, Mvi, d, m.rms_eps, h_verify, partials, pending, (int64_t)Mvi * d, st);
+    } else {
+        ProfScope ps(ctx, SSD_PROF_OTHER);
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, Mvi, d, m.rms_eps, h_verify, partials, pending, split_stride, st);
+    }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }

@@ -49,6 +49,21 @@ void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, con
 }
 
 // ---------------------------------------------------------------------------------------------
+// dst[r] = src[row_idx[r]] for rows of row_bytes (a multiple of 16) bytes.
+__global__ void __launch_bounds__(256) gather_rows_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ row_idx,
+                                                          int chunks, uint4* __restrict__ dst) {
+    const uint4* s = src + (int64_t)row_idx[blockIdx.x] * chunks;
+    uint4* d = dst + (int64_t)blockIdx.x * chunks;
+    for (int i = threadIdx.x; i < chunks; i += 256) d[i] = s[i];
+}
+
+void launch_gather_rows(const void* src, const int32_t* row_idx, int n_rows, int64_t row_bytes, void* dst, hipStream_t st) {
+    if (n_rows <= 0) return;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(n_rows), dim3(256), 0, st, static_cast<const uint4*>(src), row_idx,
+                       (int)(row_bytes / 16), static_cast<uint4*>(dst));
+}
+
+// ---------------------------------------------------------------------------------------------
 // RMSNorm: out[r] = x[row] * gain / sqrt(mean(x[row]^2) + eps), row = row_idx ? row_idx[r] : r.
 // One wavefront per row; statistics in fp32.  d must be a multiple of 4.
 // T = bf16 gain with f16 output (MFMA operand type), or fp32 gain with fp32 output.

@@ -31,11 +31,11 @@ def _tau_for(wl, q=1.9):
     return float(np.exp(-np.log(wl.model.vocab) - s * s / 2 - q * s))
 
 
-def _run_gpu(wl, weights, vi, tau, want_greedy=True):
+def _run_gpu(wl, weights, vi, tau, want_greedy=True, reserve_tokens=None):
     from paper_2603_11243_amd.binding import Context
     ctx = Context(wl.model, weights)
     M = int(vi.cu_speech[-1] + vi.cu_prompt[-1] + vi.cu_draft[-1])
-    ctx.reserve(max_tokens=M, max_verify_rows=int(vi.cu_draft[-1]), max_utts=len(vi.cu_draft) - 1)
+    ctx.reserve(max_tokens=reserve_tokens or M, max_verify_rows=int(vi.cu_draft[-1]), max_utts=len(vi.cu_draft) - 1)
     p_ids, d_ids = _dev(vi.prompt_ids), _dev(vi.draft_ids)
     hv = ctx.verify_forward(vi.speech_emb.cuda(), vi.cu_speech, p_ids, vi.cu_prompt, d_ids, vi.cu_draft)
     out = ctx.accept_prefix(hv, d_ids, vi.cu_draft, tau, want_greedy=want_greedy)
@@ -182,7 +182,8 @@ def test_bf16_row_counts_around_tile_and_split_thresholds(M):
     vi = VerifyInputs(sp, cu(S), rng.integers(0, wl.model.vocab, sum(P)).astype(np.int32), cu(P),
                       rng.integers(0, wl.model.vocab, sum(U)).astype(np.int32), cu(U))
     tau = _tau_for(wl)
-    res = _run_gpu(wl, w, vi, tau)
+    # a workspace reserved for a somewhat larger batch must also serve the few-row path (split-K scratch)
+    res = _run_gpu(wl, w, vi, tau, reserve_tokens=M + 40 if M in (33, 128) else None)
     worst = _compare(wl, w, vi, res, tau)
     assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a dropped tile would be O(1)
 
