@@ -32,8 +32,11 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
     __shared__ __align__(16) f16_t Vt[ATT_HD * ATT_V_STRIDE];
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int hgrp = lane / 32, lcol = lane % 32;
-    const AttnTile t = tiles[blockIdx.x];
-    const int kvh = blockIdx.y;
+    // work index = tile * n_kv_heads + kv head, dealt so that one XCD walks a contiguous run: the tiles of
+    // an utterance (which re-read its keys and values) then share an L2
+    const int work = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const AttnTile t = tiles[work / n_kv_heads];
+    const int kvh = work % n_kv_heads;
     const int head = kvh * RATIO + wave / 2;
     const int d_q = n_q_heads * ATT_HD, d_kv = n_kv_heads * ATT_HD;
     const int ldq = d_q + 2 * d_kv;
@@ -186,7 +189,7 @@ void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles,
                       int n_kv_heads, hipStream_t st) {
     if (n_tiles <= 0) return;
     const int ratio = n_q_heads / n_kv_heads;
-    const dim3 grid(n_tiles, n_kv_heads);
+    const dim3 grid(n_tiles * n_kv_heads);
     if (ratio == 1) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(128), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
     else if (ratio == 2) hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
     else if (ratio == 3) hipLaunchKernelGGL(attn_mfma_kernel<3>, grid, dim3(384), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
