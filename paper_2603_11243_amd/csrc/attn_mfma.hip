@@ -21,15 +21,24 @@ constexpr int ATT_HD = 128;
 constexpr int ATT_KB = 64;                    // keys per block
 constexpr int ATT_K_STRIDE = ATT_HD + 8;      // Ks[key][dim], elements
 constexpr int ATT_V_STRIDE = ATT_KB + 8;      // Vt[dim][slot], elements
+// register-resident staging values: a native vector type (struct-typed arrays that are filled under a
+// condition end up in scratch memory)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int RATIO>      // query heads per KV head
-__global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
+__global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
                                                                 const AttnTile* __restrict__ tiles, int n_q_heads,
                                                                 int n_kv_heads) {
     constexpr int NT = 128 * RATIO;
     constexpr int STAGE_ITERS = (ATT_KB * 16 + NT - 1) / NT;      // 16-byte chunks of a 64 x 128 block per thread
-    __shared__ __align__(16) f16_t Ks[ATT_KB * ATT_K_STRIDE];
-    __shared__ __align__(16) f16_t Vt[ATT_HD * ATT_V_STRIDE];
+    // LDS: the K / V^T block, and (before the first and after the last block) one 32-row staging tile per
+    // wavefront through which Q comes in and O goes out, so that global memory sees whole 256-byte rows
+    constexpr int KV_BYTES = (ATT_KB * ATT_K_STRIDE + ATT_HD * ATT_V_STRIDE) * 2;
+    constexpr int WAVE_BYTES = 32 * ATT_K_STRIDE * 2;
+    constexpr int SMEM_BYTES = KV_BYTES > 2 * RATIO * WAVE_BYTES ? KV_BYTES : 2 * RATIO * WAVE_BYTES;
+    __shared__ __align__(16) unsigned char smem[SMEM_BYTES];
+    f16_t* Ks = reinterpret_cast<f16_t*>(smem);
+    f16_t* Vt = Ks + ATT_KB * ATT_K_STRIDE;
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int hgrp = lane / 32, lcol = lane % 32;
     // work index = tile * n_kv_heads + kv head, dealt so that one XCD walks a contiguous run: the tiles of
@@ -48,13 +57,17 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
     const int qpos = q_first + lcol;
     const bool wave_live = q_first < t.seq_len;
 
-    // Q^T fragments: lane supplies query row qpos, dims 16*kk + 8*hgrp .. +8
-    f16x8_t qf[8];
-    {
-        const int qrow = min(qpos, t.seq_len - 1);
-        const uint4* src = reinterpret_cast<const uint4*>(seq + (int64_t)qrow * ldq + head * ATT_HD + hgrp * 8);
+    // Q^T fragments: lane supplies query row qpos, dims 16*kk + 8*hgrp .. +8.  The 32 x 128 tile is read
+    // from global memory row by row (16 lanes per 256-byte row) and redistributed through LDS; the loads
+    // are issued here, the redistribution follows once the first K/V loads are in flight too.
+    f16_t* wtile = reinterpret_cast<f16_t*>(smem + wave * WAVE_BYTES);
+    u32x4_t qrow[8] = {};
+    if (wave_live) {
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) qf[kk] = as_f16x8(src[kk * 2]);
+        for (int i = 0; i < 8; ++i) {
+            const int row = min(q_first + i * 4 + lane / 16, t.seq_len - 1);
+            qrow[i] = *reinterpret_cast<const u32x4_t*>(seq + (int64_t)row * ldq + head * ATT_HD + (lane % 16) * 8);
+        }
     }
     f32x16_t o_acc[4];
 #pragma unroll
@@ -66,37 +79,62 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
 
     const int kv_end = min(t.seq_len, t.q_start + 64);              // keys needed by this tile
     // K/V blocks go global -> registers -> LDS; the registers of block kb+1 are loaded while block kb
-    // is being multiplied.  K: thread owns (key = c/16, 8 dims) -> coalesced rows.  V: thread owns
-    // (key = tid%64, 8 dims) so that a wavefront writes 64 neighbouring keys of one V^T row.
-    uint4 k_reg[STAGE_ITERS], v_reg[STAGE_ITERS];
+    // is being multiplied.  K: thread owns (key = c/16, 8 dims) -> coalesced rows.  V: thread owns a pair
+    // of neighbouring keys and 8 dims, so that it writes whole dwords of V^T (two keys of one dim).
+    constexpr int PAIR_ITERS = (ATT_KB / 2 * 16 + NT - 1) / NT;
+    u32x4_t k_reg[STAGE_ITERS] = {}, v_reg[PAIR_ITERS][2] = {};
     auto load_kv = [&](int kb) {
 #pragma unroll
         for (int it = 0; it < STAGE_ITERS; ++it) {
             const int c = tid + it * NT;
             if (c < ATT_KB * 16) {
                 const int krow = min(kb + c / 16, t.seq_len - 1);
-                k_reg[it] = *reinterpret_cast<const uint4*>(kbase + (int64_t)krow * ldq + (c % 16) * 8);
-                const int vrow = min(kb + c % 64, t.seq_len - 1);
-                v_reg[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)vrow * ldq + (c / 64) * 8);
+                k_reg[it] = *reinterpret_cast<const u32x4_t*>(kbase + (int64_t)krow * ldq + (c % 16) * 8);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < PAIR_ITERS; ++it) {
+            const int q = tid + it * NT;
+            if (q < ATT_KB / 2 * 16) {
+                const int key = kb + 2 * (q % 32), dc = q / 32;
+                v_reg[it][0] = *reinterpret_cast<const u32x4_t*>(vbase + (int64_t)min(key, t.seq_len - 1) * ldq + dc * 8);
+                v_reg[it][1] = *reinterpret_cast<const u32x4_t*>(vbase + (int64_t)min(key + 1, t.seq_len - 1) * ldq + dc * 8);
             }
         }
     };
     load_kv(0);
+    f16x8_t qf[8];
+    if (wave_live) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<u32x4_t*>(wtile + (i * 4 + lane / 16) * ATT_K_STRIDE + (lane % 16) * 8) = qrow[i];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            qf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(wtile + lcol * ATT_K_STRIDE + kk * 16 + hgrp * 8));
+    }
+    __syncthreads();                 // every wavefront has its Q fragments: the staging tiles may be overwritten
     for (int kb = 0; kb < kv_end; kb += ATT_KB) {
         // ---- stage K (row-major) and V (transposed, permuted) blocks
 #pragma unroll
         for (int it = 0; it < STAGE_ITERS; ++it) {
             const int c = tid + it * NT;
-            if (c < ATT_KB * 16) {
-                *reinterpret_cast<uint4*>(Ks + (c / 16) * ATT_K_STRIDE + (c % 16) * 8) = k_reg[it];
-                const int key = c % 64, dc = c / 64;
-                const uint4 vv = v_reg[it];
-                const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
-                f16_t* vd = Vt + (dc * 8) * ATT_V_STRIDE + slot;
-                vd[0 * ATT_V_STRIDE] = (f16_t)(vv.x & 0xffff); vd[1 * ATT_V_STRIDE] = (f16_t)(vv.x >> 16);
-                vd[2 * ATT_V_STRIDE] = (f16_t)(vv.y & 0xffff); vd[3 * ATT_V_STRIDE] = (f16_t)(vv.y >> 16);
-                vd[4 * ATT_V_STRIDE] = (f16_t)(vv.z & 0xffff); vd[5 * ATT_V_STRIDE] = (f16_t)(vv.z >> 16);
-                vd[6 * ATT_V_STRIDE] = (f16_t)(vv.w & 0xffff); vd[7 * ATT_V_STRIDE] = (f16_t)(vv.w >> 16);
+            if (c < ATT_KB * 16)
+                *reinterpret_cast<u32x4_t*>(Ks + (c / 16) * ATT_K_STRIDE + (c % 16) * 8) = k_reg[it];
+        }
+#pragma unroll
+        for (int it = 0; it < PAIR_ITERS; ++it) {
+            const int q = tid + it * NT;
+            if (q < ATT_KB / 2 * 16) {
+                const int key = 2 * (q % 32), dc = q / 32;
+                const int slot = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);      // even; key+1 -> slot+1
+                uint32_t* vd = reinterpret_cast<uint32_t*>(Vt + (dc * 8) * ATT_V_STRIDE + slot);
+                const u32x4_t a = v_reg[it][0], b = v_reg[it][1];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    vd[(2 * e) * (ATT_V_STRIDE / 2)] = (a[e] & 0xffffu) | (b[e] << 16);
+                    vd[(2 * e + 1) * (ATT_V_STRIDE / 2)] = (a[e] >> 16) | (b[e] & 0xffff0000u);
+                }
             }
         }
         if (kb + ATT_KB < kv_end) load_kv(kb + ATT_KB);
@@ -132,7 +170,7 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
                 for (int r = 0; r < 16; ++r) bm = fmaxf(bm, s_acc[c][r]);
             bm = fmaxf(bm, __shfl_xor(bm, 32));
             const float m_new = fmaxf(m_run, bm);
-            const float alpha = exp2f((m_run - m_new) * sc);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
             const float ms = m_new * sc;
             float rs = 0.f;
             f16x8_t pf[4];
@@ -143,8 +181,8 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
                     uint32_t w[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p0 = exp2f(fmaf(s_acc[c][8 * s + 2 * e], sc, -ms));
-                        const float p1 = exp2f(fmaf(s_acc[c][8 * s + 2 * e + 1], sc, -ms));
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[c][8 * s + 2 * e], sc, -ms));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[c][8 * s + 2 * e + 1], sc, -ms));
                         rs += p0 + p1;
                         w[e] = pack_f16x2(p0, p1);
                     }
@@ -169,9 +207,9 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
         }
         __syncthreads();
     }
-    if (qpos < t.seq_len) {
+    // the loop ended with a barrier: K / V^T are dead, the staging tiles are free again
+    if (wave_live) {
         const float inv = 1.0f / l_run;
-        f16_t* o = out + (int64_t)(t.seq_start + qpos) * d_q + head * ATT_HD;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -180,8 +218,16 @@ __global__ void __launch_bounds__(128 * RATIO) attn_mfma_kernel(const f16_t* __r
                 uint2 w;
                 w.x = pack_f16x2(o_acc[db][4 * g] * inv, o_acc[db][4 * g + 1] * inv);
                 w.y = pack_f16x2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
-                *reinterpret_cast<uint2*>(o + dim) = w;
+                *reinterpret_cast<uint2*>(wtile + lcol * ATT_K_STRIDE + dim) = w;
             }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = q_first + i * 4 + lane / 16;
+            const uint4 w = *reinterpret_cast<const uint4*>(wtile + (i * 4 + lane / 16) * ATT_K_STRIDE + (lane % 16) * 8);
+            if (row < t.seq_len)
+                *reinterpret_cast<uint4*>(out + (int64_t)(t.seq_start + row) * d_q + head * ATT_HD + (lane % 16) * 8) = w;
+        }
     }
 }
 
