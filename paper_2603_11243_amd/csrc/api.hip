@@ -713,8 +713,8 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
         { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
         pending = 1;
         if (m.dtype == SSD_BF16) {
-            { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l], st); }
-            if (kv_start) { ProfScope ps(ctx, SSD_PROF_OTHER); launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
+                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
             float* xr = x; const void* attr = att; int rows = Mi;
             if (l == m.n_layers - 1) {
@@ -884,8 +884,8 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
             launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
             pending = 1;
             if (m.dtype == SSD_BF16) {
-                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l], st);
-                launch_kv_store(m.dtype, qkv, d_slot, Br, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
+                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
+                                     d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), st);
                 launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
                 pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
                 launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);

@@ -56,14 +56,20 @@ struct EpiResidual {
 struct EpiQkvRope {
     f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
+    // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
+    const int32_t* row_slot; f16_t* kc; f16_t* vc; int d_q;
     template <int TM, int TN>
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert(TN % 2 == 0, "rotation partners live in block pairs");
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            int p_row[16];
+            int p_row[16], slot[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) p_row[r] = pos[min(row0 + acc_row(i, r, lane), M - 1)];
+            for (int r = 0; r < 16; ++r) {
+                const int row = min(row0 + acc_row(i, r, lane), M - 1);
+                p_row[r] = pos[row];
+                slot[r] = row_slot ? row_slot[row] : -1;
+            }
 #pragma unroll
             for (int j = 0; j < TN; j += 2) {
                 const int p = col0 + j * 32;                    // packed column of this block pair (multiple of 64)
@@ -81,8 +87,15 @@ struct EpiQkvRope {
                     if (row >= M) continue;
                     const float a = acc[i][j][r] * descale, b = acc[i][j + 1][r] * descale;
                     f16_t* o = qkv + (int64_t)row * ldq;
-                    o[c0] = f32_to_f16(a * cs[r].x - b * cs[r].y);
-                    o[c1] = f32_to_f16(b * cs[r].x + a * cs[r].y);
+                    const f16_t v0 = f32_to_f16(a * cs[r].x - b * cs[r].y), v1 = f32_to_f16(b * cs[r].x + a * cs[r].y);
+                    o[c0] = v0;
+                    o[c1] = v1;
+                    if (slot[r] >= 0 && c0 >= d_q) {              // a block pair lies inside q, k or v
+                        const int d_kv = d_rot - d_q;
+                        f16_t* dst = (rot ? kc : vc) + (int64_t)slot[r] * d_kv - (rot ? d_q : d_rot);
+                        dst[c0] = v0;
+                        dst[c1] = v1;
+                    }
                 }
             }
         }
@@ -202,9 +215,10 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K,
 }
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
-                          const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale, hipStream_t st) {
+                          const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st) {
     const int N = d_q + 2 * d_kv;
-    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab)};
+    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q};
     launch_by_shape(A, Wqkv_packed, M, N, d_model, epi, st);
 }
 

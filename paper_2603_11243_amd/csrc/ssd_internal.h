@@ -68,9 +68,11 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 
 // ---- gemm_mfma.hip (f16 MFMA GEMMs with fused epilogues), attn_mfma.hip, lmhead_mfma.hip.
 // Activations and converted weights are IEEE half bit patterns; `descale` undoes the weight scale.
+// row_slot / kc / vc (all or none): rows with row_slot[row] >= 0 also store their rotated k part and their v
+// part into the K/V cache of this layer at that slot (what launch_kv_store does as a separate pass)
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
-                          hipStream_t st);
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st);
 constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
 constexpr int SKINNY_MAX_SPLITS = 8;
 int gemm_residual_splits(int M, int N, int K);
