@@ -19,8 +19,9 @@
  *   - Return value: SSD_OK or a negative ssd_status.  Argument errors are detected on the host
  *     before anything is launched, so on a non-zero return no output buffer has been written.
  *     ssd_last_error gives a message for the last failing call on that context.
- *   - Device memory is allocated only by ssd_create (re-laid-out weights, small tables) and freed by
- *     ssd_destroy.  All activations live in the caller-provided workspace (ssd_set_workspace).
+ *   - Device memory is allocated only by ssd_create and ssd_set_ctc_head (re-laid-out weights, small
+ *     tables) and freed by ssd_destroy.  All activations live in the caller-provided workspace
+ *     (ssd_set_workspace).
  *   - One context must not be used from two host threads at once.
  */
 #ifndef SSD_H
@@ -91,7 +92,8 @@ void ssd_destroy(ssd_ctx *ctx);
 
 /* Bytes of workspace needed for calls with at most max_frames CTC frames, max_tokens decoder rows
  * (sum over utterances of speech + prompt + draft), max_verify_rows draft tokens and max_utts
- * utterances.  The workspace is a dev buffer, 256-byte aligned, handed over with
+ * utterances (ctc_head_gate is covered once an output layer has been set: ask again after
+ * ssd_set_ctc_head).  The workspace is a dev buffer, 256-byte aligned, handed over with
  * ssd_set_workspace and owned by the caller; it may be replaced between calls. */
 size_t ssd_workspace_bytes(const ssd_ctx *ctx, int64_t max_frames, int64_t max_tokens,
                            int64_t max_verify_rows, int64_t max_utts);
