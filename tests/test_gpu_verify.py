@@ -188,6 +188,41 @@ def test_bf16_row_counts_around_tile_and_split_thresholds(M):
     assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a dropped tile would be O(1)
 
 
+def test_bf16_empty_drafts_and_single_row_utterances():
+    """bf16 path, two 1B-width layers: utterances without a draft inside a batch (vacuous acceptance), an
+    utterance made of one speech row, and a batch in which nobody has a draft (nothing to score)."""
+    from workloads.synth import VerifyInputs
+    from paper_2603_11243_amd.binding import Context
+    wl = scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=2, B=5)
+    w = make_model_weights(wl.model, 99, device="cuda")
+    rng = np.random.default_rng(8)
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    g = torch.Generator(device="cuda").manual_seed(8)
+    S, P, U = [1, 40, 70, 3, 90], [0, 6, 0, 2, 12], [3, 0, 65, 0, 130]
+    sp = (torch.randn(sum(S), wl.model.d_model, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    vi = VerifyInputs(sp, cu(S), rng.integers(0, wl.model.vocab, sum(P)).astype(np.int32), cu(P),
+                      rng.integers(0, wl.model.vocab, sum(U)).astype(np.int32), cu(U))
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    _compare(wl, w, vi, res, tau)
+    for b in (1, 3):
+        assert res["accept_len"][b] == 0 and res["all_accepted"][b] == 1
+    # nobody has a draft: the forward runs (K/V would be complete), nothing is scored
+    ctx = Context(wl.model, w)
+    try:
+        ctx.reserve(max_tokens=sum(S) + sum(P), max_verify_rows=0, max_utts=5)
+        p_ids = _dev(vi.prompt_ids)
+        d_ids = torch.zeros(0, dtype=torch.int32, device="cuda")
+        zero = np.zeros(6, np.int32)
+        hv = ctx.verify_forward(sp, vi.cu_speech, p_ids, vi.cu_prompt, d_ids, zero)
+        out = ctx.accept_prefix(hv, d_ids, zero, tau)
+        torch.cuda.synchronize()
+        assert hv.shape[0] == 0
+        assert out["accept_len"].cpu().tolist() == [0] * 5 and out["all_accepted"].cpu().tolist() == [1] * 5
+    finally:
+        ctx.close()
+
+
 # ------------------------------------------------------------------ bf16, full depth, sampled utterances
 
 @pytest.mark.parametrize("name,n_sample", [("cfg2_1b_b1", 1), ("cfg3_1b_ragged64", 2), ("cfg4_1b_long_ml", 1),
