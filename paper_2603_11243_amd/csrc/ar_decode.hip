@@ -132,14 +132,20 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
 // head_dim 128 in half precision: lane = (key group kg of 4, chunk dc of 8 dims).  A block of 64 keys
 // is 16 loads of K and 16 of V per lane, all issued before the first use (the rows are 256 bytes, a
 // 16-lane group reads one row); a score is a 16-lane reduction, the softmax statistics are reduced over
-// the four key groups, and P.V accumulates in the lane (no LDS), reduced over the key groups at the end.
-__global__ void __launch_bounds__(64) decode_attn_hd128_kernel(const f16_t* __restrict__ qkv, const f16_t* __restrict__ kc,
+// the four key groups, and P.V accumulates in the lane, reduced over the key groups at the end.
+// A workgroup is DEC_WAVES wavefronts that take the 64-key blocks of one (utterance, head) in turn and
+// merge their (max, sum, output) triples through LDS: the blocks of a context are then loaded at
+// once instead of one after the other.
+constexpr int DEC_WAVES = 4;
+__global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const f16_t* __restrict__ qkv, const f16_t* __restrict__ kc,
                                                                const f16_t* __restrict__ vc, const int32_t* __restrict__ kv_start,
                                                                const int32_t* __restrict__ n_ctx, int n_q_heads, int n_kv_heads,
                                                                f16_t* __restrict__ out) {
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
     constexpr int HD = 128;
-    const int lane = threadIdx.x, kg = lane / 16, dc = lane % 16;
+    __shared__ float merge_o[DEC_WAVES][16][8];
+    __shared__ float merge_ml[DEC_WAVES][2];
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64, kg = lane / 16, dc = lane % 16;
     const int b = blockIdx.x, h = blockIdx.y;
     const int kvh = h / (n_q_heads / n_kv_heads);
     const int d_q = n_q_heads * HD, d_kv = n_kv_heads * HD;
@@ -152,7 +158,7 @@ __global__ void __launch_bounds__(64) decode_attn_hd128_kernel(const f16_t* __re
     const f16_t* kbase = kc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
     const f16_t* vbase = vc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
     float m = -INFINITY, l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < n; k0 += 64) {
+    for (int k0 = wave * 64; k0 < n; k0 += 64 * DEC_WAVES) {
         uint4 kr[16], vr[16];
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
@@ -201,7 +207,28 @@ __global__ void __launch_bounds__(64) decode_attn_hd128_kernel(const f16_t* __re
         o[e] += __shfl_xor(o[e], 16);
         o[e] += __shfl_xor(o[e], 32);
     }
+    // merge the wavefronts: wave w's partial is (m, l, o) with o scaled by 2^-m; a wavefront without a block has l = 0
     if (kg == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) merge_o[wave][dc][e] = o[e];
+        if (dc == 0) { merge_ml[wave][0] = m; merge_ml[wave][1] = l; }
+    }
+    __syncthreads();
+    if (wave == 0 && kg == 0) {
+        float mt = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < DEC_WAVES; ++w) mt = fmaxf(mt, merge_ml[w][0]);     // finite: wave 0 saw key 0
+        l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < DEC_WAVES; ++w) {
+            const float lw = merge_ml[w][1];
+            const float f = lw > 0.f ? __builtin_amdgcn_exp2f(merge_ml[w][0] - mt) : 0.f;
+            l = fmaf(lw, f, l);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(merge_o[w][dc][e], f, o[e]);
+        }
         const float inv = 1.0f / l;
         uint4 w;
         w.x = pack_f16x2(o[0] * inv, o[1] * inv); w.y = pack_f16x2(o[2] * inv, o[3] * inv);
@@ -215,7 +242,7 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
                         hipStream_t st) {
     if (Br <= 0) return;
     if (dtype == SSD_BF16 && head_dim == 128)
-        hipLaunchKernelGGL(decode_attn_hd128_kernel, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+        hipLaunchKernelGGL(decode_attn_hd128_kernel, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
                            (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out);
     else if (dtype == SSD_BF16)
         hipLaunchKernelGGL(decode_attn_kernel<f16_t>, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
