@@ -101,6 +101,13 @@ int ssd_set_workspace(ssd_ctx *ctx, void *dev_ptr, size_t bytes);
 
 const char *ssd_last_error(const ssd_ctx *ctx);
 
+/* Conditions that only the device sees (they depend on data in device memory) do not fail a call: the
+ * kernels repair them and raise a sticky flag.  ssd_device_flags waits for the stream, writes the flags
+ * raised since the last call to *flags (host) and clears them.
+ *   SSD_FLAG_TOKEN_CLAMPED  a prompt, draft or first_tok id outside [0, vocab) was clamped into range */
+enum ssd_device_flag { SSD_FLAG_TOKEN_CLAMPED = 1 };
+int ssd_device_flags(ssd_ctx *ctx, int32_t *flags /*host*/);
+
 /* Measurement aid (no counterpart in the paper): times kernel launches with HIP events recorded on
  * the context's stream.  ssd_profile_select chooses what the following calls bracket: one class,
  * SSD_PROF_ALL, or SSD_PROF_OFF (default; no events are recorded).  It waits for the stream and

@@ -20,7 +20,7 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
-           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate"]
+           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.ssd_accept_grid.restype = i32
     lib.ssd_plan_batches.argtypes = [vp, i32, i64, i32, vp, vp, vp]
     lib.ssd_plan_batches.restype = i32
+    lib.ssd_device_flags.argtypes = [vp, vp]
+    lib.ssd_device_flags.restype = i32
     lib.ssd_set_ctc_head.argtypes = [vp, vp, vp, i32, i32]
     lib.ssd_set_ctc_head.restype = i32
     lib.ctc_head_gate.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, vp, vp, vp]
@@ -193,6 +195,12 @@ class Context:
     def set_workspace(self, buf: Optional[torch.Tensor]):
         self._ws = buf
         self._check(self._lib.ssd_set_workspace(self._h, _ptr(buf), 0 if buf is None else buf.numel()))
+
+    def device_flags(self) -> int:
+        """Sticky flags raised by kernels since the last call (waits for the stream); 1 = a token id was clamped."""
+        f = C.c_int32(0)
+        self._check(self._lib.ssd_device_flags(self._h, C.byref(f)))
+        return int(f.value)
 
     def profile_select(self, kernel_class):
         k = PROF_CLASSES.index(kernel_class) if isinstance(kernel_class, str) else kernel_class

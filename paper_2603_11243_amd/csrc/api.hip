@@ -90,6 +90,7 @@ struct ssd_ctx {
     std::vector<float> ds_qkv, ds_o, ds_gu, ds_down;
     float ds_lm = 1.f;
     float* rope_tab = nullptr;               // [max_positions][head_dim/2] (cos, sin) pairs
+    int32_t* dev_flags = nullptr;            // sticky data-dependent conditions seen by kernels (ssd_device_flags)
     void* ws = nullptr;
     size_t ws_bytes = 0;
     uint16_t* head_w = nullptr;              // CTC output layer, padded with zero rows (bias -inf there)
@@ -364,6 +365,8 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
     if ((e = dev_alloc((void**)&c->rope_tab, tab.size() * 4)) != hipSuccess) return bail(e, "hipMalloc(rope)");
     if ((e = hipMemcpyAsync(c->rope_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
         return bail(e, "hipMemcpyAsync(rope)");
+    if ((e = dev_alloc((void**)&c->dev_flags, 256)) != hipSuccess) return bail(e, "hipMalloc(flags)");
+    if ((e = hipMemsetAsync(c->dev_flags, 0, 256, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(flags)");
     if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "weight packing");
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "weight packing launch");
     *out = c;
@@ -393,6 +396,16 @@ size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_t
         need = std::max(need, plan_accept(ctx->cfg, max_verify_rows, max_utts).total);
     }
     return need + 256;
+}
+
+int ssd_device_flags(ssd_ctx* ctx, int32_t* flags) {
+    if (!ctx || !flags) return SSD_EINVAL;
+    *flags = 0;
+    if (!ctx->dev_flags) return SSD_OK;
+    HIP_TRY(ctx, hipMemcpyAsync(flags, ctx->dev_flags, 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (*flags) HIP_TRY(ctx, hipMemsetAsync(ctx->dev_flags, 0, 4, ctx->stream));
+    return SSD_OK;
 }
 
 int ssd_set_workspace(ssd_ctx* ctx, void* dev_ptr, size_t bytes) {
@@ -698,7 +711,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     hipStream_t st = ctx->stream;
     const int Mi = (int)M, d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
 
-    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, st); }
+    { ProfScope ps(ctx, SSD_PROF_OTHER); launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, ctx->dev_flags, st); }
     float* partials = reinterpret_cast<float*>(ws + p.partials);
     const int64_t split_stride = (int64_t)Mi * d;
     int pending = 1;            // K splits of the last residual projection still to be added to x (1: none)
@@ -878,7 +891,7 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
         const int32_t* d_pos = reinterpret_cast<const int32_t*>(ws + p.pos) + (size_t)t * Br;
         const int32_t* d_nctx = reinterpret_cast<const int32_t*>(ws + p.n_ctx) + (size_t)t * Br;
         const int32_t* d_slot = reinterpret_cast<const int32_t*>(ws + p.slot) + (size_t)t * Br;
-        launch_embed_rows(m.dtype, nullptr, ctx->embed, nullptr, tok_in, d_row_src, Br, d, m.vocab, x, st);
+        launch_embed_rows(m.dtype, nullptr, ctx->embed, nullptr, tok_in, d_row_src, Br, d, m.vocab, x, ctx->dev_flags, st);
         int pending = 1;
         for (int l = 0; l < m.n_layers; ++l) {
             launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);

@@ -15,17 +15,14 @@ __global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ s
                                                          const int32_t* __restrict__ prompt_ids,
                                                          const int32_t* __restrict__ draft_ids,
                                                          const int32_t* __restrict__ row_src, int M, int d, int vocab,
-                                                         float* __restrict__ x) {
+                                                         float* __restrict__ x, int32_t* __restrict__ flags) {
     const int r = blockIdx.x;
     const int32_t code = row_src[r];
     const T* src;
-    if (code & SRC_DRAFT) {
-        int id = draft_ids[code & SRC_MASK];
-        id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
-        src = embed + (int64_t)id * d;
-    } else if (code & SRC_PROMPT) {
-        int id = prompt_ids[code & SRC_MASK];
-        id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    if (code & (SRC_DRAFT | SRC_PROMPT)) {
+        const int raw = (code & SRC_DRAFT) ? draft_ids[code & SRC_MASK] : prompt_ids[code & SRC_MASK];
+        const int id = raw < 0 ? 0 : (raw >= vocab ? vocab - 1 : raw);
+        if (id != raw && flags && threadIdx.x == 0) *flags = SSD_FLAG_TOKEN_CLAMPED;   // sticky until read
         src = embed + (int64_t)id * d;
     } else {
         src = speech_emb + (int64_t)code * d;
@@ -38,14 +35,14 @@ __global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ s
 
 void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
                        const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
-                       hipStream_t st) {
+                       int32_t* flags, hipStream_t st) {
     if (M <= 0) return;
     if (dtype == SSD_BF16)
         hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, st, (const bf16_t*)speech_emb,
-                           (const bf16_t*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x);
+                           (const bf16_t*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x, flags);
     else
         hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(M), dim3(256), 0, st, (const float*)speech_emb,
-                           (const float*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x);
+                           (const float*)embed, prompt_ids, draft_ids, row_src, M, d, vocab, x, flags);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -45,9 +45,10 @@ struct AttnTile {
 };
 
 // ---- elementwise.hip
+// flags (may be NULL): *flags = SSD_FLAG_TOKEN_CLAMPED if a token id had to be clamped into [0, vocab)
 void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
                        const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
-                       hipStream_t st);
+                       int32_t* flags, hipStream_t st);
 void launch_gather_rows(const void* src, const int32_t* row_idx, int n_rows, int64_t row_bytes, void* dst, hipStream_t st);
 // a = rmsnorm(x) * gain;  rows optionally gathered through row_idx (NULL = identity).
 // If n_splits > 1, x[row] is first increased by partials[s][row] for s = 0..n_splits-1 (fixed order;

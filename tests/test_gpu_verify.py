@@ -124,6 +124,32 @@ def test_tiny_f32_sharper_model_and_edge_shapes():
     assert res["accept_len"][1] == 0 and res["all_accepted"][1] == 1          # empty draft: vacuous accept
 
 
+def test_out_of_range_token_ids_are_clamped_and_flagged():
+    """Ids outside [0, vocab) cannot be seen by the host: the device clamps them and raises a sticky flag."""
+    from paper_2603_11243_amd.binding import Context
+    from workloads.synth import VerifyInputs
+    wl = WORKLOADS["cfg1_tiny_f32"]
+    w = make_model_weights(wl.model, 5)
+    V = wl.model.vocab
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    g = torch.Generator().manual_seed(2)
+    sp = torch.randn(12, wl.model.d_model, generator=g) * 0.02
+    bad_p, bad_d = np.array([3, -7, V + 5], np.int32), np.array([10, V, 20, -1], np.int32)
+    ok_p, ok_d = np.clip(bad_p, 0, V - 1), np.clip(bad_d, 0, V - 1)
+    ctx = Context(wl.model, w)
+    try:
+        ctx.reserve(max_tokens=32, max_verify_rows=8, max_utts=1)
+        run = lambda p, d: ctx.accept_prefix(ctx.verify_forward(sp.cuda(), cu([12]), _dev(p), cu([3]), _dev(d), cu([4])),
+                                             _dev(d), cu([4]), 1e-5)["draft_logp"].cpu().numpy()
+        good = run(ok_p, ok_d)
+        assert ctx.device_flags() == 0
+        clamped = run(bad_p, bad_d)
+        assert ctx.device_flags() == 1 and ctx.device_flags() == 0          # reported once, then cleared
+        assert np.array_equal(good, clamped)
+    finally:
+        ctx.close()
+
+
 def test_tiny_f32_causality_and_batch_isolation():
     wl = WORKLOADS["cfg1_tiny_f32"]
     cb = make_ctc_batch(wl)
