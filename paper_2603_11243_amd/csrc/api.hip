@@ -85,6 +85,8 @@ struct ssd_ctx {
     const void* norm_final = nullptr;
     std::vector<const void*> wo, w_down, norm_attn, norm_mlp;   // wo / w_down: what the GEMMs read
     std::vector<void*> wqkv, wgu;            // library-owned fused layouts
+    // bf16 models: second copy of the four projection matrices in the layout of the few-row kernel (or NULL)
+    std::vector<void*> s_qkv, s_o, s_gu, s_down;
     std::vector<void*> owned;                // every device allocation made by ssd_create
     // bf16 models: weights live as f16 * 2^k; these undo the scale in the GEMM epilogues
     std::vector<float> ds_qkv, ds_o, ds_gu, ds_down;
@@ -340,6 +342,16 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
             launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, scale[4 * l + 1], c->stream);
             launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, scale[4 * l + 3], c->stream);
             c->wo.push_back(po); c->w_down.push_back(pd);
+            struct { const void* src; int N, K; std::vector<void*>* dst; } copies[4] = {
+                {pq, dq + 2 * dkv, d, &c->s_qkv}, {po, d, dq, &c->s_o}, {pg, 2 * dff, d, &c->s_gu}, {pd, d, dff, &c->s_down}};
+            for (auto& cp : copies) {
+                void* ps = nullptr;
+                if (stream_layout_supported(cp.N, cp.K)) {
+                    if ((e = dev_alloc(&ps, (size_t)cp.N * cp.K * 2)) != hipSuccess) return bail(e, "hipMalloc(stream layout)");
+                    launch_stream_layout((const uint16_t*)cp.src, ps, cp.N, cp.K, c->stream);
+                }
+                cp.dst->push_back(ps);
+            }
         } else {
             c->wo.push_back(w->wo[l]); c->w_down.push_back(w->w_down[l]);
         }
@@ -726,7 +738,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
         { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
         pending = 1;
         if (m.dtype == SSD_BF16) {
-            { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
+            { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
                                                                          kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
             float* xr = x; const void* attr = att; int rows = Mi;
@@ -737,11 +749,11 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
                 xr = x_c; attr = att_c; rows = Mvi; compact = true;
             }
             const int64_t stride = (int64_t)rows * d;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], xr, partials, rows, d, dq, ctx->ds_o[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], ctx->s_o[l], xr, partials, rows, d, dq, ctx->ds_o[l], st); }
             { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, st); }
             pending = 1;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
@@ -897,14 +909,14 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
             launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
             pending = 1;
             if (m.dtype == SSD_BF16) {
-                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
+                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
                                      d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), st);
                 launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
-                pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
+                pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
                 launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
                 pending = 1;
-                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], st);
-                pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], st);
+                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], st);
+                pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], st);
             } else {
                 float* gu = reinterpret_cast<float*>(ws + p.gu);
                 launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Br, dq + 2 * dkv, d, F32_STORE, st);

@@ -78,7 +78,9 @@ struct GemmTile {
     // aligned.  Slices kt0 <= kt < kt1 of K are accumulated (K itself is the row stride of A and W).
     static __device__ __forceinline__ void run(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int K,
                                                int m0, int n0, int kt0, int kt1, unsigned char* smem,
-                                               f32x16_t (&acc)[TM][TN], int n_rows_w = 0x7fffffff) {
+                                               f32x16_t (&acc)[TM][TN], int n_rows_w = 0x7fffffff, int lda = 0, int ldw = 0) {
+        if (lda == 0) lda = K;                               // row strides in elements (default: dense rows)
+        if (ldw == 0) ldw = K;
         const int tid = threadIdx.x, lane = tid % 64;
         const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
         const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -92,12 +94,12 @@ struct GemmTile {
         for (int i = 0; i < A_LOADS; ++i) {
             const int r = (i * WAVES + wave) * 8 + lrow;
             const int grow = min(m0 + r, M - 1);
-            a_off[i] = (unsigned)grow * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
+            a_off[i] = (unsigned)grow * (unsigned)lda * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
         }
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
             const int r = (i * WAVES + wave) * 8 + lrow;
-            b_off[i] = (unsigned)min(n0 + r, n_rows_w - 1) * (unsigned)K * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
+            b_off[i] = (unsigned)min(n0 + r, n_rows_w - 1) * (unsigned)ldw * 2u + (unsigned)((lslot ^ ((r >> 1) & 7)) * 16);
         }
         auto issue_loads = [&](int kt, int stage) {
             unsigned char* sa = smem + stage * STAGE_BYTES;

@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "gemm_core.h"
+#include "gemm_stream.h"
 #include "ssd_internal.h"
 
 namespace ssd {
@@ -30,6 +31,7 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_
 // through an unrelated pointer cannot be moved ahead of it by the compiler, and a read-modify-write
 // written element by element degenerates into one exposed memory round trip per element.
 struct EpiResidual {
+    static constexpr bool WANTS_SPLIT = false;
     float* x; int ldx; float descale;
     template <int TM, int TN>
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -54,6 +56,7 @@ struct EpiResidual {
 };
 
 struct EpiQkvRope {
+    static constexpr bool WANTS_SPLIT = false;
     f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
@@ -103,6 +106,7 @@ struct EpiQkvRope {
 };
 
 struct EpiSwiglu {
+    static constexpr bool WANTS_SPLIT = false;
     f16_t* h; int d_ff; float descale;
     template <int TM, int TN>
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -126,6 +130,7 @@ struct EpiSwiglu {
 // Stores the scaled accumulator as an fp32 partial sum of one K split: part[split][row][col].
 // Whoever consumes it (the RMSNorm that follows) adds the splits in a fixed order.
 struct EpiPartial {
+    static constexpr bool WANTS_SPLIT = true;
     float* part; int ld; int64_t split_stride; float descale;
     template <int TM, int TN>
     __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
@@ -164,7 +169,7 @@ gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M
     Tile::run(A, W, M, K, tm * BM, tn * BN, kt0, kt1, smem_raw, acc);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    if constexpr (std::is_same<Epi, EpiPartial>::value)
+    if constexpr (Epi::WANTS_SPLIT)
         epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane, split);
     else
         epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
@@ -184,22 +189,64 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
     hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, splits, epi);
 }
 
+// Register-streaming kernel for at most 32 rows (gemm_stream.h); it reads the stream-layout copy of the
+// weights.  A workgroup takes K/64/splits steps of 64; they must divide evenly over 8 or 4 wavefronts.
+constexpr int STREAM_MAX_ROWS = 32;
+template <int NW, int DEPTH, class Epi>
+static void launch_stream_cfg(const f16_t* A, const void* Ws, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
+    auto kern = gemm_stream_kernel<NW, DEPTH, Epi>;
+    constexpr size_t lds = gemm_stream_lds_bytes<NW, DEPTH>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((N / 64) * splits), dim3(64 * NW), lds, st, A, static_cast<const u32x4_t*>(Ws), M, N, K, splits, epi);
+}
+bool stream_layout_supported(int N, int K) { return N > 0 && K > 0 && N % 64 == 0 && K % 256 == 0; }
+static bool stream_shape_ok(int M, int N, int K, int splits) {
+    if (M <= 0 || M > STREAM_MAX_ROWS || !stream_layout_supported(N, K) || splits < 1) return false;
+    if ((int64_t)M * K * 2 >= (int64_t)1 << 32) return false;
+    const int KT = K / 64;
+    return KT % splits == 0 && (KT / splits) % 4 == 0;
+}
+template <class Epi>
+static bool try_launch_stream(const f16_t* A, const void* Ws, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
+    if (!Ws || !stream_shape_ok(M, N, K, splits)) return false;
+    const int per = K / 64 / splits;
+    const int nw = per % 8 == 0 ? 8 : 4;
+    const int steps = per / nw;
+    const int depth = steps % 4 == 0 ? 4 : steps % 3 == 0 ? 3 : steps % 2 == 0 ? 2 : 1;
+#define SSD_STREAM_CASE(NW_, D_) if (nw == NW_ && depth == D_) { launch_stream_cfg<NW_, D_>(A, Ws, M, N, K, splits, epi, st); return true; }
+    SSD_STREAM_CASE(8, 4) SSD_STREAM_CASE(8, 3) SSD_STREAM_CASE(8, 2) SSD_STREAM_CASE(8, 1)
+    SSD_STREAM_CASE(4, 4) SSD_STREAM_CASE(4, 3) SSD_STREAM_CASE(4, 2) SSD_STREAM_CASE(4, 1)
+#undef SSD_STREAM_CASE
+    return false;
+}
+void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_t st) {
+    const int64_t units = (int64_t)N * K / 8;
+    hipLaunchKernelGGL(stream_layout_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<const u32x4_t*>(w), static_cast<u32x4_t*>(out), N, K);
+}
+
 // Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
 // of 256 for every GEMM here); the tile height is picked per launch so that the number of tiles
 // wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
 // With at most 128 rows the job is weight streaming and what counts is the number of weight bytes in
-// flight: a skinny 128 x 64 tile (four wavefronts, each 32 rows x 64 columns) with a six-stage LDS ring
+// flight: at most 32 rows go to the register-streaming kernel when the shape divides evenly; otherwise a
+// skinny 128 x 64 tile (four wavefronts, each 32 rows x 64 columns) with a six-stage LDS ring
 // (144 KB, five slices in flight), and for at most 32 rows a 32 x 64 tile of one wavefront, six stages
 // of 12 KB, two workgroups per CU.
 template <class Epi>
-static void launch_skinny(const f16_t* A, const f16_t* W, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
+static void launch_skinny(const f16_t* A, const f16_t* W, const void* Ws, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
+    if (try_launch_stream(A, Ws, M, N, K, splits, epi, st)) return;
     if (M <= 32) launch_gemm<32, 64, 1, 1, 6>(A, W, M, N, K, splits, epi, st);
     else launch_gemm<128, 64, 4, 1, 6>(A, W, M, N, K, splits, epi, st);
 }
 
 template <class Epi>
-static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
-    if (M <= SKINNY_MAX_ROWS) { launch_skinny(A, W, M, N, K, 1, epi, st); return; }
+static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= SKINNY_MAX_ROWS) { launch_skinny(A, W, Ws, M, N, K, 1, epi, st); return; }
     const int heights[3] = {256, 192, 128};
     const double eff[3] = {1.0, 0.97, 0.90};
     int best = 0;
@@ -214,16 +261,21 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, int M, int N, int K,
     else launch_gemm<128, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
 }
 
-void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
+void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
                           const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st) {
     const int N = d_q + 2 * d_kv;
     EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q};
-    launch_by_shape(A, Wqkv_packed, M, N, d_model, epi, st);
+    launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
 }
 
-int gemm_residual_splits(int M, int N, int K) {
+int gemm_residual_splits(int M, int N, int K, bool have_stream) {
     if (M > SKINNY_MAX_ROWS) return 1;
+    if (have_stream && M <= STREAM_MAX_ROWS) {
+        // register-streaming kernel: the most splits (workgroups) whose K range still divides over 4 wavefronts
+        for (int s = SKINNY_MAX_SPLITS; s >= 2; --s)
+            if (stream_shape_ok(M, N, K, s) && (N / 64) * s <= 512) return s;
+    }
     int splits = 1;
     while (splits < SKINNY_MAX_SPLITS && (N / 64) * splits < 256 && K / GEMM_BK / (splits * 2) >= 4) splits *= 2;
     return splits;
@@ -233,23 +285,23 @@ int gemm_residual_splits(int M, int N, int K) {
 // of them for weight streaming; the splits land in `partials` ([splits][M][N] fp32) and the caller
 // hands them to the next RMSNorm, which adds them to x in a fixed order.  Returns the split count
 // (1: x has been updated in place).
-int launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, float* partials, int M, int N, int K,
+int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
                          float descale, hipStream_t st) {
-    const int splits = gemm_residual_splits(M, N, K);
+    const int splits = gemm_residual_splits(M, N, K, W_stream != nullptr);
     if (splits > 1) {
         EpiPartial epi{partials, N, (int64_t)M * N, descale};
-        launch_skinny(A, W, M, N, K, splits, epi, st);
+        launch_skinny(A, W, W_stream, M, N, K, splits, epi, st);
         return splits;
     }
     EpiResidual epi{x, N, descale};
-    launch_by_shape(A, W, M, N, K, epi, st);
+    launch_by_shape(A, W, W_stream, M, N, K, epi, st);
     return 1;
 }
 
-void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
+void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
                         float descale, hipStream_t st) {
     EpiSwiglu epi{h, d_ff, descale};
-    launch_by_shape(A, Wgu_packed, M, 2 * d_ff, K, epi, st);
+    launch_by_shape(A, Wgu_packed, W_stream, M, 2 * d_ff, K, epi, st);
 }
 
 }  // namespace ssd

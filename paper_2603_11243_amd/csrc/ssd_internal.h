@@ -71,17 +71,22 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 // Activations and converted weights are IEEE half bit patterns; `descale` undoes the weight scale.
 // row_slot / kc / vc (all or none): rows with row_slot[row] >= 0 also store their rotated k part and their v
 // part into the K/V cache of this layer at that slot (what launch_kv_store does as a separate pass)
-void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, uint16_t* qkv, const int32_t* pos,
+// W_stream (may be NULL): the same weights in the stream layout of launch_stream_layout, read when at
+// most 32 rows are projected
+void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
                           const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st);
 constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
 constexpr int SKINNY_MAX_SPLITS = 8;
-int gemm_residual_splits(int M, int N, int K);
+int gemm_residual_splits(int M, int N, int K, bool have_stream);
 // returns the number of K splits written to `partials` ([splits][M][N] fp32), or 1 if x was updated in place
-int launch_gemm_residual(const uint16_t* A, const uint16_t* W, float* x, float* partials, int M, int N, int K,
+int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
                          float descale, hipStream_t st);
-void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, uint16_t* h, int M, int d_ff, int K,
+void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
                         float descale, hipStream_t st);
+// second copy of an f16 weight matrix W[N,K] for the few-row kernel (N % 64 == 0, K % 256 == 0)
+bool stream_layout_supported(int N, int K);
+void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_t st);
 void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
                       int n_kv_heads, hipStream_t st);
 // partial log-sum-exp of the LM head over column groups; see lmhead_mfma.hip
