@@ -781,7 +781,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
 
 struct ArPlan {
     size_t row_src, kv_start, pos, n_ctx, slot, meta_bytes;       // uploaded once: [Br], [Br], [steps][Br] x 3
-    size_t x, a, qkv, attn, gu, h, partials, hfin, logp, part_ms, tgt, part_arg, total;
+    size_t x, a, qkv, attn, gu, h, partials, qkv_part, hfin, logp, part_ms, tgt, part_arg, total;
 };
 ArPlan plan_ar(const ssd_model_cfg& c, int64_t Br, int64_t steps) {
     ArPlan p;
@@ -801,6 +801,8 @@ ArPlan plan_ar(const ssd_model_cfg& c, int64_t Br, int64_t steps) {
     p.gu = o; if (c.dtype == SSD_F32) o = align_up(o + (size_t)(Br * 2 * c.d_ff) * 4);
     p.h = o; o = align_up(o + (size_t)(Br * c.d_ff) * es);
     p.partials = o; if (c.dtype == SSD_BF16 && Br <= SKINNY_MAX_ROWS) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * Br * d * 4);
+    // K-split partial sums of the QKV projection (finished inside the decode attention, few rows only)
+    p.qkv_part = o; if (c.dtype == SSD_BF16 && Br <= 32) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * Br * (dq + 2 * dkv) * 4);
     p.hfin = o; o = align_up(o + (size_t)(Br * d) * es);
     p.logp = o; o = align_up(o + (size_t)Br * 4);
     p.part_ms = p.tgt = p.part_arg = o;
@@ -893,6 +895,7 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
     float* x = reinterpret_cast<float*>(ws + p.x);
     void* a = ws + p.a; void* qkv = ws + p.qkv; void* att = ws + p.attn; void* h = ws + p.h; void* hfin = ws + p.hfin;
     float* partials = reinterpret_cast<float*>(ws + p.partials);
+    float* qkv_part = reinterpret_cast<float*>(ws + p.qkv_part);
     float* logp = reinterpret_cast<float*>(ws + p.logp);
     hipStream_t st = ctx->stream;
     const int d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
@@ -909,9 +912,17 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
             launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
             pending = 1;
             if (m.dtype == SSD_BF16) {
-                launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
-                                     d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), st);
-                launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                // few rows, head_dim 128: the QKV projection stays K-split and the decode attention finishes it
+                const int qsplits = (Br <= 32 && m.head_dim == 128)
+                    ? launch_gemm_qkv_partial((const uint16_t*)a, ctx->s_qkv[l], qkv_part, Br, d, dq + 2 * dkv, ctx->ds_qkv[l], st) : 0;
+                if (qsplits) {
+                    launch_decode_attn_fused(qkv_part, qsplits, ctx->rope_tab, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br,
+                                             m.n_q_heads, m.n_kv_heads, att, st);
+                } else {
+                    launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
+                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), st);
+                    launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                }
                 pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
                 launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
                 pending = 1;

@@ -137,10 +137,61 @@ __global__ void __launch_bounds__(64) decode_attn_kernel(const T* __restrict__ q
 // merge their (max, sum, output) triples through LDS: the blocks of a context are then loaded at
 // once instead of one after the other.
 constexpr int DEC_WAVES = 4;
+
+// Fused variant: the QKV projection of the step has been left as K-split partial sums
+// part[split][row][packed column] (fp32, packed column order of the fused QKV weight: inside a head the
+// rotary pairs (i, i+64) sit 32 columns apart in 64-column groups, V columns are in natural order).
+// The kernel adds the splits, rotates q and the new k, appends the new k / v row to the cache (first query
+// head of each K/V group) and treats that row as the last key without reading it back.
+struct DecodeFused {
+    const float* part; int n_splits; int64_t split_stride;    // split_stride = rows * (d_q + 2 d_kv)
+    const float2* rope_tab;                                   // [position][64] (cos, sin)
+    f16_t* kc_w; f16_t* vc_w;                                 // writable views of the cache
+    // The new row's position is the number of rows its utterance has in the cache (cache row i of an
+    // utterance is position i), and its slot is kv_start + that number: no further index arrays.
+};
+// sum over the splits (at most 8) of eight consecutive packed columns starting at `col` of row b; the loads
+// of four splits are issued together
+__device__ __forceinline__ void sum_splits8(const DecodeFused& f, int64_t row_off, int col, float (&v)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+#pragma unroll 1
+    for (int s0 = 0; s0 < f.n_splits; s0 += 4) {
+        float4 t[4][2];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const float4* src = reinterpret_cast<const float4*>(f.part + (s0 + s < f.n_splits ? s0 + s : 0) * f.split_stride + row_off + col);
+            t[s][0] = src[0];
+            t[s][1] = src[1];
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s0 + s < f.n_splits) {
+                v[0] += t[s][0].x; v[1] += t[s][0].y; v[2] += t[s][0].z; v[3] += t[s][0].w;
+                v[4] += t[s][1].x; v[5] += t[s][1].y; v[6] += t[s][1].z; v[7] += t[s][1].w;
+            }
+        }
+    }
+}
+// dims 8 dc .. 8 dc + 7 of rotated head `head_col0` (packed column of the head's first dim) at position p
+__device__ __forceinline__ void rotated_chunk(const DecodeFused& f, int64_t row_off, int head_col0, int dc, int p, float (&v)[8]) {
+    const int i0 = (dc % 8) * 8;                              // dim inside the first half of the head
+    const int col_lo = head_col0 + (i0 / 32) * 64 + (i0 % 32);
+    float lo[8], hi[8];
+    sum_splits8(f, row_off, col_lo, lo);
+    sum_splits8(f, row_off, col_lo + 32, hi);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float2 cs = f.rope_tab[(int64_t)p * 64 + i0 + e];
+        v[e] = dc < 8 ? lo[e] * cs.x - hi[e] * cs.y : hi[e] * cs.x + lo[e] * cs.y;
+    }
+}
+
+template <bool FUSED>
 __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const f16_t* __restrict__ qkv, const f16_t* __restrict__ kc,
                                                                const f16_t* __restrict__ vc, const int32_t* __restrict__ kv_start,
                                                                const int32_t* __restrict__ n_ctx, int n_q_heads, int n_kv_heads,
-                                                               f16_t* __restrict__ out) {
+                                                               f16_t* __restrict__ out, DecodeFused fu) {
     typedef _Float16 h8 __attribute__((ext_vector_type(8)));
     constexpr int HD = 128;
     __shared__ float merge_o[DEC_WAVES][16][8];
@@ -149,17 +200,14 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
     const int b = blockIdx.x, h = blockIdx.y;
     const int kvh = h / (n_q_heads / n_kv_heads);
     const int d_q = n_q_heads * HD, d_kv = n_kv_heads * HD;
-    float qf[8];
-    load8(qkv + (int64_t)b * (d_q + 2 * d_kv) + h * HD + dc * 8, qf);
     const float sc = 0.08838834764831845f * 1.4426950408889634f;      // log2(e) / sqrt(128)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) qf[e] *= sc;
-    const int n = n_ctx[b];
+    float qf[8];
+    float m = -INFINITY, l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int n = n_ctx[b] - (FUSED ? 1 : 0);                // rows to read from the cache
     const f16_t* kbase = kc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
     const f16_t* vbase = vc + (int64_t)kv_start[b] * d_kv + kvh * HD + dc * 8;
-    float m = -INFINITY, l = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int k0 = wave * 64; k0 < n; k0 += 64 * DEC_WAVES) {
-        uint4 kr[16], vr[16];
+    uint4 kr[16], vr[16];
+    auto load_block = [&](int k0) {
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
             const int key = min(k0 + it * 4 + kg, n - 1);
@@ -170,6 +218,58 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
             const int key = min(k0 + it * 4 + kg, n - 1);
             vr[it] = *reinterpret_cast<const uint4*>(vbase + (int64_t)key * d_kv);
         }
+    };
+    // the first block of keys and values is requested before q is put together
+    if (wave * 64 < n) load_block(wave * 64);
+    if constexpr (FUSED) {
+        // Key group 0 of every wavefront builds q (wavefront 0 also the new k / v row) and hands it to the
+        // other key groups: the partial sums are read once per wavefront, not once per lane.
+        const int64_t row_off = (int64_t)b * (d_q + 2 * d_kv);
+        const int p = n;                                     // position of the new token
+        float s_new = 0.f;
+        uint4 vw = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[e] = 0.f;
+        if (kg == 0) {
+            rotated_chunk(fu, row_off, h * HD, dc, p, qf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[e] = (float)(_Float16)qf[e] * sc;      // q is rounded like a stored row
+            if (wave == 0) {
+                float kn[8], vn[8];
+                rotated_chunk(fu, row_off, d_q + kvh * HD, dc, p, kn);
+                sum_splits8(fu, row_off, d_q + d_kv + kvh * HD + dc * 8, vn);
+                // the cache holds half precision: the new row takes part in this step with the values later steps read
+                uint4 kw;
+                kw.x = pack_f16x2(kn[0], kn[1]); kw.y = pack_f16x2(kn[2], kn[3]); kw.z = pack_f16x2(kn[4], kn[5]); kw.w = pack_f16x2(kn[6], kn[7]);
+                vw.x = pack_f16x2(vn[0], vn[1]); vw.y = pack_f16x2(vn[2], vn[3]); vw.z = pack_f16x2(vn[4], vn[5]); vw.w = pack_f16x2(vn[6], vn[7]);
+                if (h % (n_q_heads / n_kv_heads) == 0) {
+                    const int64_t so = ((int64_t)kv_start[b] + n) * d_kv + kvh * HD + dc * 8;
+                    *reinterpret_cast<uint4*>(fu.kc_w + so) = kw;
+                    *reinterpret_cast<uint4*>(fu.vc_w + so) = vw;
+                }
+                const h8 kh = __builtin_bit_cast(h8, kw);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s_new = fmaf(qf[e], (float)kh[e], s_new);
+            }
+        }
+        s_new = group_allreduce<16>(s_new, OpSum());          // lanes 0..15 hold the score of the new row
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[e] = __shfl(qf[e], dc);
+        s_new = __shfl(s_new, 0);
+        if (wave == 0) {                                     // the new row is wavefront 0's first key
+            m = s_new; l = 1.f;
+            if (kg == 0) {
+                const h8 vh = __builtin_bit_cast(h8, vw);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (float)vh[e];
+            }
+        }
+    } else {
+        load8(qkv + (int64_t)b * (d_q + 2 * d_kv) + h * HD + dc * 8, qf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[e] *= sc;
+    }
+    for (int k0 = wave * 64; k0 < n; k0 += 64 * DEC_WAVES) {
         float s[16];
         float cm = -INFINITY;
 #pragma unroll
@@ -201,6 +301,7 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         ps += __shfl_xor(ps, 32);
         l = l * alpha + ps;
         m = m_new;
+        if (k0 + 64 * DEC_WAVES < n) load_block(k0 + 64 * DEC_WAVES);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -242,14 +343,24 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
                         hipStream_t st) {
     if (Br <= 0) return;
     if (dtype == SSD_BF16 && head_dim == 128)
-        hipLaunchKernelGGL(decode_attn_hd128_kernel, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
-                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out);
+        hipLaunchKernelGGL(decode_attn_hd128_kernel<false>, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, DecodeFused{});
     else if (dtype == SSD_BF16)
         hipLaunchKernelGGL(decode_attn_kernel<f16_t>, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
                            (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (f16_t*)out);
     else
         hipLaunchKernelGGL(decode_attn_kernel<float>, dim3(Br, n_q_heads), dim3(64), 0, st, (const float*)qkv, (const float*)kc,
                            (const float*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (float*)out);
+}
+
+void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
+                              const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
+                              void* out, hipStream_t st) {
+    if (Br <= 0) return;
+    const int64_t stride = (int64_t)Br * (n_q_heads + 2 * n_kv_heads) * 128;
+    DecodeFused fu{qkv_part, n_splits, stride, reinterpret_cast<const float2*>(rope_tab), (f16_t*)kc, (f16_t*)vc};
+    hipLaunchKernelGGL(decode_attn_hd128_kernel<true>, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, nullptr, (const f16_t*)kc,
+                       (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, fu);
 }
 
 }  // namespace ssd

@@ -269,6 +269,17 @@ void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const 
     launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
 }
 
+int launch_gemm_qkv_partial(const uint16_t* A, const void* W_stream, float* part, int M, int d_model, int N, float descale,
+                            hipStream_t st) {
+    if (!W_stream || M > STREAM_MAX_ROWS) return 0;
+    int splits = 0;
+    for (int s = SKINNY_MAX_SPLITS; s >= 2 && !splits; --s)                 // about one workgroup per CU
+        if (stream_shape_ok(M, N, d_model, s) && (N / 64) * s <= 320) splits = s;
+    if (!splits) return 0;
+    EpiPartial epi{part, N, (int64_t)M * N, descale};
+    return try_launch_stream(A, W_stream, M, N, d_model, splits, epi, st) ? splits : 0;
+}
+
 int gemm_residual_splits(int M, int N, int K, bool have_stream) {
     if (M > SKINNY_MAX_ROWS) return 1;
     if (have_stream && M <= STREAM_MAX_ROWS) {

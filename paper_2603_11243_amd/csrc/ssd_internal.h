@@ -114,6 +114,19 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
                         const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
                         hipStream_t st);
 
+// head_dim 128, half precision: decode attention that finishes the QKV projection itself.  qkv_part is
+// [n_splits][Br][d_q + 2 d_kv] fp32 partial sums in the packed column order of the fused QKV weight; the
+// kernel adds the splits, rotates q and k at position n_ctx[b] - 1 (the number of rows the utterance already
+// has in the cache), stores the new k / v row at cache slot kv_start[b] + n_ctx[b] - 1 and attends to the
+// cached rows plus the new one.
+void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
+                              const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
+                              void* out, hipStream_t st);
+// QKV projection left as K-split partial sums for launch_decode_attn_fused; returns the split count, or 0 if
+// the shape is not served (then nothing was launched)
+int launch_gemm_qkv_partial(const uint16_t* A, const void* W_stream, float* part, int M, int d_model, int N, float descale,
+                            hipStream_t st);
+
 // threshold grids: outputs are [n_tau][B] / [n_tau][Bv]
 void launch_gate_grid(const float* max_entropy, int B, const float* taus_dev, int n_tau, uint8_t* gate_pass, hipStream_t st);
 void launch_accept_grid(const float* logp, const int32_t* cu_draft_dev, int Bv, const float* ln_taus_dev, int n_tau,
