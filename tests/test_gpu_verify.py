@@ -190,10 +190,11 @@ def test_bf16_reduced_depth_whole_batch(name, layers, B):
     print(f"{wl.name}: worst |dlogp| = {worst:.3e} over {vi.cu_draft[-1]} tokens")
 
 
-@pytest.mark.parametrize("M", [33, 128, 129, 191, 257, 513, 770])
+@pytest.mark.parametrize("M", [9, 31, 32, 33, 128, 129, 191, 257, 513, 770])
 def test_bf16_row_counts_around_tile_and_split_thresholds(M):
     """One 1B-width layer; utterance lengths chosen so that the total row count M sits on and next to
-    the boundaries the GEMM dispatch uses (skinny path up to 128 rows, tile heights 128/192/256)."""
+    the boundaries the GEMM dispatch uses (register-streaming kernel up to 32 rows, skinny path up to 128
+    rows, tile heights 128/192/256)."""
     from workloads.synth import VerifyInputs
     wl = scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=1, B=3)
     w = make_model_weights(wl.model, 4242, device="cuda")
