@@ -281,6 +281,33 @@ def ar_fallback_leg(ctx, wl, meta, tau, n_steps=16):
                          "algorithmic_bytes_per_step": weight_bytes}}
 
 
+def library_gemm_leg(m, M, device, iters=30):
+    """The four projection shapes of one layer as plain library GEMMs (torch.matmul = hipBLASLt, IEEE half, no
+    epilogue: no RoPE, SiLU*mul or residual add), next to which the fused kernels of this library are read.
+    Operands are distributed like the real ones: normalised activations, N(0, 0.02^2) weights scaled by 2^9."""
+    shapes = {"gemm_qkv": (m.d_q + 2 * m.d_kv, m.d_model), "gemm_o": (m.d_model, m.d_q),
+              "gemm_gate_up": (2 * m.d_ff, m.d_model), "gemm_down": (m.d_model, m.d_ff)}
+    gen = torch.Generator(device=device)
+    gen.manual_seed(11)
+    out = {}
+    for name, (N, K) in shapes.items():
+        a = torch.randn(M, K, device=device, generator=gen).half()
+        w = (torch.randn(N, K, device=device, generator=gen) * (0.02 * 512)).half()
+        for _ in range(3):
+            c = a @ w.t()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(iters):
+            c = a @ w.t()
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / iters
+        out[name] = {"us": ms * 1e3, "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12}
+        del a, w, c
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -386,15 +413,31 @@ def main():
         "all_projection_gemms": {"tflops": step_gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
                                  "frac_of_peak": step_gemm_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS if gemm_ms else None},
     }
+    # per projection: flops of a step over the HIP-event time of that class in the breakdown step
+    per_gemm_flops = {"gemm_qkv": 2.0 * L * M * qkv_params, "gemm_o": 2.0 * L * rows_avg * m.d_model * m.d_q,
+                      "gemm_gate_up": 2.0 * L * rows_avg * m.d_model * 2 * m.d_ff, "gemm_down": 2.0 * L * rows_avg * m.d_model * m.d_ff}
+    out["projection_tflops"] = {k: (f / (breakdown[k] * 1e-3) / 1e12 if breakdown.get(k) else None) for k, f in per_gemm_flops.items()}
     if not args.main_only:
         tf, ghz = ctx.measure_mfma_ceiling(20000)
         out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
                                            "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
         out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
+        big = torch.empty(3 << 30, dtype=torch.uint8, device=device).fill_(1)       # far beyond the memory-side cache
+        hbm = ctx.measure_hbm_read(big, 5)
+        del big
+        out["hbm_read_ceiling_this_device"] = {"gb_per_s": hbm, "frac_of_nominal_peak": hbm / PEAK_HBM_GBS,
+                                               "what": "plain streaming read of 3 GiB, one workgroup per CU on its own contiguous share, 8 KB in flight per wavefront"}
         out["ar_fallback"] = ar_fallback_leg(ctx, wl, meta, tau)
+        if out["ar_fallback"]:
+            out["ar_fallback"]["roofline"]["frac_of_device_ceiling"] = out["ar_fallback"]["roofline"]["achieved"] / hbm
         out["gate_roofline"] = gate_roofline(ctx, wl, device)
+        out["gate_roofline"]["frac_of_device_ceiling"] = out["gate_roofline"]["achieved"] / hbm
         out["ctc_head_gate"] = ctc_head_leg(ctx, wl, device)
         out["single_utterance"] = single_utterance_leg(ctx, wl, device)
+        if m.dtype == "bf16":
+            out["library_gemm_reference"] = {"what": "torch.matmul (hipBLASLt) on the same shapes, IEEE half, plain GEMM without "
+                                                     "the fused epilogues; compare with projection_tflops", "rows": M,
+                                             **library_gemm_leg(m, M, device)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, step, weights, meta, args.cpu_budget_tokens)
     print(json.dumps(out))

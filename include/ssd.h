@@ -131,6 +131,14 @@ int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
  * and clock management leave for the matrix cores on this device.  Uses the first 256 KB of the
  * workspace and waits for the stream. */
 int ssd_measure_mfma_ceiling(ssd_ctx *ctx, int iters, float *tflops /*host*/, float *shader_ghz /*host*/);
+/* Measurement aid: reads `bytes` (rounded down to a multiple of 16) of the caller's device buffer
+ * `iters` times with a plain streaming kernel (one workgroup of eight wavefronts per CU, each
+ * walking its own contiguous share with eight 1 KB loads in flight per wavefront) and reports the sustained rate in GB/s: what this device delivers to a kernel that
+ * does nothing but read, i.e. the practical ceiling under the nominal HBM peak for the gate and the
+ * weight-streaming steps.  The buffer should be much larger than the 256 MB memory-side cache.
+ * dev_buf: device pointer, 16-byte aligned, not written.  Needs a workspace (one word of it is
+ * used) and waits for the stream.  Errors: SSD_EINVAL, SSD_EWORKSPACE, SSD_EHIP. */
+int ssd_measure_hbm_read(ssd_ctx *ctx, const void *dev_buf, size_t bytes, int iters, float *gbytes_per_s /*host*/);
 int ssd_profile_read(ssd_ctx *ctx, float *total_ms /*host [SSD_PROF_N_CLASSES]*/,
                      int32_t *launches /*host [SSD_PROF_N_CLASSES]*/);
 

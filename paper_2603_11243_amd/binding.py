@@ -18,7 +18,7 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
            -5: "SSD_EUNSUPPORTED"}
 
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
-           "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ctc_gate", "verify_forward", "accept_prefix",
+           "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ssd_measure_hbm_read", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
            "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags"]
 
@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.ssd_profile_read.restype = i32
     lib.ssd_measure_mfma_ceiling.argtypes = [vp, i32, vp, vp]
     lib.ssd_measure_mfma_ceiling.restype = i32
+    lib.ssd_measure_hbm_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
+    lib.ssd_measure_hbm_read.restype = i32
     lib.ctc_gate.argtypes = [vp, vp, i32, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.ctc_gate.restype = i32
     lib.verify_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp]
@@ -216,6 +218,11 @@ class Context:
         t, g = C.c_float(), C.c_float()
         self._check(self._lib.ssd_measure_mfma_ceiling(self._h, iters, C.byref(t), C.byref(g)))
         return float(t.value), float(g.value)
+
+    def measure_hbm_read(self, buf: torch.Tensor, iters: int = 5) -> float:
+        g = C.c_float()
+        self._check(self._lib.ssd_measure_hbm_read(self._h, buf.data_ptr(), buf.numel() * buf.element_size(), iters, C.byref(g)))
+        return float(g.value)
 
     # ---- the three calls -------------------------------------------------------------------
 

@@ -519,6 +519,29 @@ int ssd_plan_batches(const int32_t* lengths, int n, int64_t max_tokens, int padd
     return SSD_OK;
 }
 
+int ssd_measure_hbm_read(ssd_ctx* ctx, const void* dev_buf, size_t bytes, int iters, float* gbytes_per_s) {
+    if (!ctx || !dev_buf || !gbytes_per_s || iters <= 0 || bytes < 16) return SSD_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dev_buf) & 15) return fail(ctx, SSD_EINVAL, "ssd_measure_hbm_read: buffer must be 16-byte aligned");
+    if (!ctx->ws || ctx->ws_bytes < 256) return fail(ctx, SSD_EWORKSPACE, "ssd_measure_hbm_read: a workspace must be set");
+    bytes &= ~(size_t)15;
+    uint32_t* sink = static_cast<uint32_t*>(ctx->ws);
+    hipEvent_t e0, e1;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    HIP_TRY(ctx, hipEventCreate(&e1));
+    launch_hbm_read(dev_buf, bytes, sink, ctx->stream);                                   // warm-up
+    HIP_TRY(ctx, hipEventRecord(e0, ctx->stream));
+    for (int i = 0; i < iters; ++i) launch_hbm_read(dev_buf, bytes, sink, ctx->stream);
+    HIP_TRY(ctx, hipEventRecord(e1, ctx->stream));
+    HIP_TRY(ctx, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *gbytes_per_s = (float)((double)bytes * iters / (ms * 1e-3) / 1e9);
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
 int ssd_measure_mfma_ceiling(ssd_ctx* ctx, int iters, float* tflops, float* shader_ghz) {
     if (!ctx || !tflops || !shader_ghz || iters <= 0) return SSD_EINVAL;
     const int n_wg = 256;                                  // one workgroup of four wavefronts per CU
