@@ -402,7 +402,7 @@ def main():
         "gate_pass_rate": float(g["gate_pass"].float().mean().cpu()),
         "full_accept_rate": float(acc["all_accepted"].float().mean().cpu()),
         "mean_accepted_prefix_frac": float(np.mean(acc_len / np.maximum(np.diff(meta["cu_d"]), 1))),
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel<EpiSwiglu> (gate/up projection + SiLU*mul)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma16_kernel<EpiSwiglu> (gate/up projection + SiLU*mul)",
                      "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_MFMA_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "traffic_unit": "bytes per launch (L2<->fabric, incl. Infinity Cache hits)",

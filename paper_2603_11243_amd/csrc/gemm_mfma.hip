@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "gemm_core.h"
+#include "gemm_core16.h"
 #include "gemm_stream.h"
 #include "ssd_internal.h"
 
@@ -30,27 +31,38 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_
 // The epilogues below read first and write afterwards, block by block: a load placed after a store
 // through an unrelated pointer cannot be moved ahead of it by the compiler, and a read-modify-write
 // written element by element degenerates into one exposed memory round trip per element.
+// They are written against an accumulator layout L (Layout32: 32x32 blocks of v_mfma_f32_32x32x16,
+// Layout16: 16x16 blocks of v_mfma_f32_16x16x32): L::row / L::col give the element a register holds and
+// L::PAIR the distance, in blocks, to the block 32 columns further (where the fused weight layouts put
+// the partner column).
 struct EpiResidual {
     static constexpr bool WANTS_SPLIT = false;
     float* x; int ldx; float descale;
-    template <int TM, int TN>
-    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        constexpr int G0 = 32 / (L::REGS * TN);              // row blocks per batch: about 32 loads in flight
+        constexpr int G = (G0 >= 1 && TM % (G0 >= 1 ? G0 : 1) == 0) ? G0 : 1;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            float old[16][TN];
+        for (int i0 = 0; i0 < TM; i0 += G) {
+            float old[G][L::REGS][TN];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = min(row0 + acc_row(i, r, lane), M - 1);
+            for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) old[r][j] = x[(int64_t)row * ldx + col0 + acc_col(j, lane)];
-            }
+                for (int r = 0; r < L::REGS; ++r) {
+                    const int row = min(row0 + L::row(i0 + g, r, lane), M - 1);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + acc_row(i, r, lane);
-                if (row >= M) continue;
+                    for (int j = 0; j < TN; ++j) old[g][r][j] = x[(int64_t)row * ldx + col0 + L::col(j, lane)];
+                }
 #pragma unroll
-                for (int j = 0; j < TN; ++j) x[(int64_t)row * ldx + col0 + acc_col(j, lane)] = old[r][j] + acc[i][j][r] * descale;
-            }
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int r = 0; r < L::REGS; ++r) {
+                    const int row = row0 + L::row(i0 + g, r, lane);
+                    if (row >= M) continue;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        x[(int64_t)row * ldx + col0 + L::col(j, lane)] = old[g][r][j] + acc[i0 + g][j][r] * descale;
+                }
         }
     }
 };
@@ -61,39 +73,40 @@ struct EpiQkvRope {
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
     const int32_t* row_slot; f16_t* kc; f16_t* vc; int d_q;
-    template <int TM, int TN>
-    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
-        static_assert(TN % 2 == 0, "rotation partners live in block pairs");
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        static_assert((TN * L::BLOCK) % 64 == 0, "rotation partners live 32 packed columns apart in groups of 64");
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            int p_row[16], slot[16];
+            int p_row[L::REGS], slot[L::REGS];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = min(row0 + acc_row(i, r, lane), M - 1);
+            for (int r = 0; r < L::REGS; ++r) {
+                const int row = min(row0 + L::row(i, r, lane), M - 1);
                 p_row[r] = pos[row];
                 slot[r] = row_slot ? row_slot[row] : -1;
             }
 #pragma unroll
-            for (int j = 0; j < TN; j += 2) {
-                const int p = col0 + j * 32;                    // packed column of this block pair (multiple of 64)
+            for (int j = 0; j < TN; ++j) {
+                if ((j / L::PAIR) % 2 != 0) continue;           // second half of a group of 64: handled with its partner
+                const int p = col0 + j * L::BLOCK;              // packed column of this block
                 const bool rot = p < d_rot;
-                const int head = p / 128, grp = (p % 128) / 64;
-                const int i_rot = grp * 32 + lane % 32;
-                const int c0 = rot ? head * 128 + i_rot : p + lane % 32;
+                const int head = p / 128, grp = (p % 128) / 64, off = p % 32;
+                const int i_rot = grp * 32 + off + lane % L::BLOCK;
+                const int c0 = rot ? head * 128 + i_rot : p + lane % L::BLOCK;
                 const int c1 = rot ? c0 + 64 : c0 + 32;
-                float2 cs[16];
+                float2 cs[L::REGS];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) cs[r] = rot ? rope_tab[(int64_t)p_row[r] * 64 + i_rot] : make_float2(1.f, 0.f);
+                for (int r = 0; r < L::REGS; ++r) cs[r] = rot ? rope_tab[(int64_t)p_row[r] * 64 + i_rot] : make_float2(1.f, 0.f);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = row0 + acc_row(i, r, lane);
+                for (int r = 0; r < L::REGS; ++r) {
+                    const int row = row0 + L::row(i, r, lane);
                     if (row >= M) continue;
-                    const float a = acc[i][j][r] * descale, b = acc[i][j + 1][r] * descale;
+                    const float a = acc[i][j][r] * descale, b = acc[i][j + L::PAIR][r] * descale;
                     f16_t* o = qkv + (int64_t)row * ldq;
                     const f16_t v0 = f32_to_f16(a * cs[r].x - b * cs[r].y), v1 = f32_to_f16(b * cs[r].x + a * cs[r].y);
                     o[c0] = v0;
                     o[c1] = v1;
-                    if (slot[r] >= 0 && c0 >= d_q) {              // a block pair lies inside q, k or v
+                    if (slot[r] >= 0 && c0 >= d_q) {              // a group of 64 lies inside q, k or v
                         const int d_kv = d_rot - d_q;
                         f16_t* dst = (rot ? kc : vc) + (int64_t)slot[r] * d_kv - (rot ? d_q : d_rot);
                         dst[c0] = v0;
@@ -108,19 +121,21 @@ struct EpiQkvRope {
 struct EpiSwiglu {
     static constexpr bool WANTS_SPLIT = false;
     f16_t* h; int d_ff; float descale;
-    template <int TM, int TN>
-    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
-        static_assert(TN % 2 == 0, "gate/up live in block pairs");
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        static_assert((TN * L::BLOCK) % 64 == 0, "gate/up live 32 packed columns apart in groups of 64");
 #pragma unroll
-        for (int j = 0; j < TN; j += 2) {
-            const int f = (col0 + j * 32) / 2 + lane % 32;
+        for (int j = 0; j < TN; ++j) {
+            if ((j / L::PAIR) % 2 != 0) continue;
+            const int p = col0 + j * L::BLOCK;
+            const int f = (p / 64) * 32 + p % 32 + lane % L::BLOCK;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = row0 + acc_row(i, r, lane);
+                for (int r = 0; r < L::REGS; ++r) {
+                    const int row = row0 + L::row(i, r, lane);
                     if (row >= M) continue;
-                    const float g = acc[i][j][r] * descale, u = acc[i][j + 1][r] * descale;
+                    const float g = acc[i][j][r] * descale, u = acc[i][j + L::PAIR][r] * descale;
                     h[(int64_t)row * d_ff + f] = f32_to_f16(g / (1.0f + __expf(-g)) * u);
                 }
         }
@@ -132,17 +147,17 @@ struct EpiSwiglu {
 struct EpiPartial {
     static constexpr bool WANTS_SPLIT = true;
     float* part; int ld; int64_t split_stride; float descale;
-    template <int TM, int TN>
-    __device__ __forceinline__ void operator()(f32x16_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
         float* base = part + split * split_stride;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + acc_row(i, r, lane);
+            for (int r = 0; r < L::REGS; ++r) {
+                const int row = row0 + L::row(i, r, lane);
                 if (row >= M) continue;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) base[(int64_t)row * ld + col0 + acc_col(j, lane)] = acc[i][j][r] * descale;
+                for (int j = 0; j < TN; ++j) base[(int64_t)row * ld + col0 + L::col(j, lane)] = acc[i][j][r] * descale;
             }
     }
 };
@@ -189,6 +204,42 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
     hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, splits, epi);
 }
 
+// Big tiles on v_mfma_f32_16x16x32_f16 (gemm_core16.h): same tile shapes, workgroup order and epilogues.
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
+gemm_mfma16_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
+    using Tile = GemmTile16<BM, BN, WAVES_M, WAVES_N>;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    f32x4_t acc[Tile::TM][Tile::TN];
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+    Tile::run(A, W, M, K, tm * BM, tn * BN, 0, K / GEMM_BK, smem_raw, acc);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    epi.template operator()<Tile::TM, Tile::TN, Layout16>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
+static void launch_gemm16(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= 0) return;
+    auto kern = gemm_mfma16_kernel<BM, BN, WAVES_M, WAVES_N, Epi>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, 2>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    const int tiles = ((M + BM - 1) / BM) * (N / BN);
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, epi);
+}
+
 // Register-streaming kernel for at most 32 rows (gemm_stream.h); it reads the stream-layout copy of the
 // weights.  A workgroup takes K/64/splits steps of 64; they must divide evenly over 8 or 4 wavefronts.
 constexpr int STREAM_MAX_ROWS = 32;
@@ -230,7 +281,7 @@ void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_
 }
 
 // Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
-// of 256 for every GEMM here); the tile height is picked per launch so that the number of tiles
+// of 256 for every GEMM here) on the 16x16x32 matrix instruction; the tile height is picked per launch so that the number of tiles
 // wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
 // With at most 128 rows the job is weight streaming and what counts is the number of weight bytes in
 // flight: at most 32 rows go to the register-streaming kernel when the shape divides evenly; otherwise a
@@ -256,9 +307,9 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int 
         const double cost = (double)((tiles + 255) / 256) * heights[c] / eff[c];
         if (cost < best_cost - 1e-9) { best_cost = cost; best = c; }
     }
-    if (best == 0) launch_gemm<256, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
-    else if (best == 1) launch_gemm<192, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
-    else launch_gemm<128, 256, 2, 4, 2>(A, W, M, N, K, 1, epi, st);
+    if (best == 0) launch_gemm16<256, 256, 2, 4>(A, W, M, N, K, epi, st);
+    else if (best == 1) launch_gemm16<192, 256, 2, 4>(A, W, M, N, K, epi, st);
+    else launch_gemm16<128, 256, 2, 4>(A, W, M, N, K, epi, st);
 }
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
