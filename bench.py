@@ -420,7 +420,7 @@ def main():
     if not args.main_only:
         tf, ghz = ctx.measure_mfma_ceiling(20000)
         out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,
-                                           "what": "MFMA-only loop, random f16 operands in registers, 4 wavefronts per CU"}
+                                           "what": "MFMA-only loop (v_mfma_f32_16x16x32_f16), random f16 operands in registers, 8 wavefronts per CU"}
         out["roofline"]["frac_of_device_ceiling"] = achieved / tf if tf else None
         big = torch.empty(3 << 30, dtype=torch.uint8, device=device).fill_(1)       # far beyond the memory-side cache
         hbm = ctx.measure_hbm_read(big, 5)

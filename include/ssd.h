@@ -125,10 +125,10 @@ enum ssd_prof_class {
     SSD_PROF_N_CLASSES = 10
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
-/* Measurement aid: runs `iters` rounds of 8 independent v_mfma_f32_32x32x16_f16 per wavefront on
- * pseudo-random register operands, four wavefronts on every CU, no memory traffic, and reports the
+/* Measurement aid: runs `iters` rounds of 16 independent v_mfma_f32_16x16x32_f16 per wavefront on
+ * pseudo-random register operands, eight wavefronts on every CU, no memory traffic, and reports the
  * sustained rate (TFLOP/s) and the shader clock observed meanwhile (GHz): the ceiling that power
- * and clock management leave for the matrix cores on this device.  Uses the first 256 KB of the
+ * and clock management leave for the matrix cores on this device.  Uses the first 513 KB of the
  * workspace and waits for the stream. */
 int ssd_measure_mfma_ceiling(ssd_ctx *ctx, int iters, float *tflops /*host*/, float *shader_ghz /*host*/);
 /* Measurement aid: reads `bytes` (rounded down to a multiple of 16) of the caller's device buffer

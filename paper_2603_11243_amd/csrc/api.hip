@@ -544,11 +544,11 @@ int ssd_measure_hbm_read(ssd_ctx* ctx, const void* dev_buf, size_t bytes, int it
 
 int ssd_measure_mfma_ceiling(ssd_ctx* ctx, int iters, float* tflops, float* shader_ghz) {
     if (!ctx || !tflops || !shader_ghz || iters <= 0) return SSD_EINVAL;
-    const int n_wg = 256;                                  // one workgroup of four wavefronts per CU
-    const size_t need = (size_t)n_wg * 256 * 4 + 256;
+    const int n_wg = 256;                                  // one workgroup of eight wavefronts per CU
+    const size_t need = (size_t)n_wg * 512 * 4 + 256;
     if (!ctx->ws || ctx->ws_bytes < need) return fail(ctx, SSD_EWORKSPACE, "ssd_measure_mfma_ceiling: workspace of %zu bytes needed", need);
     float* sink = static_cast<float*>(ctx->ws);
-    long long* clocks = reinterpret_cast<long long*>(static_cast<char*>(ctx->ws) + (size_t)n_wg * 256 * 4);
+    long long* clocks = reinterpret_cast<long long*>(static_cast<char*>(ctx->ws) + (size_t)n_wg * 512 * 4);
     hipEvent_t e0, e1;
     HIP_TRY(ctx, hipEventCreate(&e0));
     HIP_TRY(ctx, hipEventCreate(&e1));
@@ -563,7 +563,7 @@ int ssd_measure_mfma_ceiling(ssd_ctx* ctx, int iters, float* tflops, float* shad
     HIP_TRY(ctx, hipMemcpy(hc, clocks, sizeof hc, hipMemcpyDeviceToHost));
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    const double flops = (double)n_wg * 4 * (double)iters * 8 * 32768.0;      // 32x32x16 MFMA = 32768 flop
+    const double flops = (double)n_wg * 8 * (double)iters * 16 * 16384.0;    // 16x16x32 MFMA = 16384 flop
     *tflops = (float)(flops / (ms * 1e-3) / 1e12);
     *shader_ghz = (float)((double)hc[0] / ((double)hc[1] * 10.0));            // constant clock ticks at 100 MHz
     return SSD_OK;

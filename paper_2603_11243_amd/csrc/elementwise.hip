@@ -375,21 +375,22 @@ void launch_accept_scan(const float* logp, const int32_t* cu_draft_dev, int Bv, 
 
 // ---------------------------------------------------------------------------------------------
 // Measurement aid: what the matrix cores sustain on this device with nothing else going on.
-// Every wavefront issues independent v_mfma_f32_32x32x16_f16 on pseudo-random operands held in
-// registers (no memory traffic in the loop); one wavefront also samples the shader clock against
-// the 100 MHz constant clock.
+// Every wavefront issues independent v_mfma_f32_16x16x32_f16 (the instruction of the big GEMMs, and the one
+// that sustains the most flop/s under the power limit) on pseudo-random operands held in registers (no
+// memory traffic in the loop), two wavefronts per SIMD; one wavefront also samples the shader clock
+// against the 100 MHz constant clock.
 typedef _Float16 peak_f16x8_t __attribute__((ext_vector_type(8)));
-typedef float peak_f32x16_t __attribute__((ext_vector_type(16)));
-__global__ void __launch_bounds__(256) mfma_ceiling_kernel(float* __restrict__ sink, long long* __restrict__ clocks, int iters) {
-    peak_f32x16_t acc[8];
+typedef float peak_f32x4_t __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* __restrict__ sink, long long* __restrict__ clocks, int iters) {
+    peak_f32x4_t acc[16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 16; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    peak_f16x8_t a[4], b[2];
+        for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+    peak_f16x8_t a[8], b[2];
     unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < 8; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) { h = h * 1664525u + 1013904223u; a[q][e] = (_Float16)(((h >> 8) & 0xffff) / 65536.0f - 0.5f); }
 #pragma unroll
@@ -399,15 +400,15 @@ __global__ void __launch_bounds__(256) mfma_ceiling_kernel(float* __restrict__ s
     const long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i % 4], b[i / 4], acc[i], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i % 8], b[i / 8], acc[i], 0, 0, 0);
     }
     if (blockIdx.x == 3 && threadIdx.x == 0) { clocks[0] = clock64() - c0; clocks[1] = wall_clock64() - w0; }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 16; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s += acc[i][r];
-    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+        for (int r = 0; r < 4; ++r) s += acc[i][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
 // Streaming read of n 16-byte units: every workgroup (eight wavefronts) walks its own contiguous share,
@@ -435,7 +436,7 @@ void launch_hbm_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t 
 }
 
 void launch_mfma_ceiling(float* sink, long long* clocks, int n_workgroups, int iters, hipStream_t st) {
-    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(n_workgroups), dim3(256), 0, st, sink, clocks, iters);
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(n_workgroups), dim3(512), 0, st, sink, clocks, iters);
 }
 
 }  // namespace ssd

@@ -132,7 +132,7 @@ void launch_gate_grid(const float* max_entropy, int B, const float* taus_dev, in
 void launch_accept_grid(const float* logp, const int32_t* cu_draft_dev, int Bv, const float* ln_taus_dev, int n_tau,
                         int32_t* accept_len, uint8_t* all_accepted, hipStream_t st);
 
-// measurement aid: MFMA-only loop (sink: n_workgroups*256 floats, clocks: 2 x int64)
+// measurement aid: MFMA-only loop (sink: n_workgroups*512 floats, clocks: 2 x int64)
 // measurement aid: plain streaming read of `bytes` (multiple of 16) from buf
 void launch_hbm_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
 void launch_mfma_ceiling(float* sink, long long* clocks, int n_workgroups, int iters, hipStream_t st);
