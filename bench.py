@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0
 
 # Memory traffic of the dominant kernel per launch, from two rocprofv3 --pmc runs of this file
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a
-# plain 1 GiB device copy (`--copy-reference`): FETCH_SIZE reads 524300 for 1048576 KiB (factor 2.0),
+# plain 1 GiB device copy (`--copy-reference`): FETCH_SIZE reads 524301 for 1048576 KiB (factor 2.0),
 # WRITE_SIZE reads 1048576 (factor 1.0).  See profiles/pmc_traffic_gemm_gate_up_cfg3.md.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_1b_ragged64": (329845.2 * 2.0 + 82304.0 * 1.0) * 1024.0,      # a full layer (5144 rows)
+    "cfg3_1b_ragged64": (356406.3 * 2.0 + 84095.4 * 1.0) * 1024.0,      # a full layer (5144 rows)
 }
 
 
