@@ -40,3 +40,20 @@ def test_gate_and_accept_grids_match_oracle():
     assert (got_len[:-1] >= got_len[1:]).all()
     assert np.array_equal(got_len[0], U) and (got_len[-1] == 0).all()
     ctx.close()
+
+
+def test_measurement_aids_report_plausible_ceilings():
+    """The two measured denominators of bench.py: an MFMA-only loop and a plain streaming read.  Both are
+    bounded by the chip's nominal peaks (2.5 PFLOP/s, 8 TB/s) and must not come out absurdly low either;
+    a buffer that is not 16-byte aligned is an argument error."""
+    from paper_2603_11243_amd.binding import Context, SsdError
+    ctx = Context()
+    ctx.reserve(max_frames=200000, max_utts=64)         # the MFMA loop uses 513 KB of the workspace
+    tf, ghz = ctx.measure_mfma_ceiling(2000)
+    assert 300.0 < tf < 2500.0 and 0.5 < ghz < 2.6
+    buf = torch.ones(1 << 28, dtype=torch.uint8, device="cuda")
+    gbs = ctx.measure_hbm_read(buf, 3)
+    assert 1000.0 < gbs < 16000.0                        # 256 MB may partly sit in the memory-side cache
+    with pytest.raises(SsdError):
+        ctx.measure_hbm_read(buf[1:], 1)
+    ctx.close()
