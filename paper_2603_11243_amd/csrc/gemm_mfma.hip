@@ -5,7 +5,11 @@
 // Every epilogue first multiplies the accumulator by `descale`, the inverse of the power of two the
 // weight tensor was scaled by when it was converted to f16.
 // The fused weight layouts are produced by pack_qkv_kernel / pack_gate_up_kernel: a column and the
-// column it must be combined with sit in neighbouring 32-wide accumulator blocks of the same lane.
+// column it must be combined with sit 32 packed columns apart inside a group of 64, i.e. in two
+// accumulator blocks of the same lane.
+// Three main loops feed these epilogues: big tiles on v_mfma_f32_16x16x32_f16 (gemm_core16.h), skinny
+// LDS-ring tiles for 33..128 rows (gemm_core.h) and the register-streaming kernel for at most 32 rows
+// (gemm_stream.h).
 #include <type_traits>
 
 #include "gemm_core.h"
@@ -283,8 +287,9 @@ void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_
 }
 
 // Tile choice.  All candidates use eight wavefronts as 2 x 4 and a 256-wide tile (N is a multiple
-// of 256 for every GEMM here) on the 16x16x32 matrix instruction; the tile height is picked per launch so that the number of tiles
-// wastes as little of the last round over the 256 CUs as possible: cost = rounds * height / efficiency.
+// of 256 for every GEMM here) on the 16x16x32 matrix instruction; the tile height is picked per launch
+// so that the number of tiles wastes as little of the last round over the 256 CUs as possible:
+// cost = rounds * height / efficiency.
 // With at most 128 rows the job is weight streaming and what counts is the number of weight bytes in
 // flight: at most 32 rows go to the register-streaming kernel when the shape divides evenly; otherwise a
 // skinny 128 x 64 tile (four wavefronts, each 32 rows x 64 columns) with a six-stage LDS ring
