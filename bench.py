@@ -320,7 +320,17 @@ def main():
                     help="skip the side legs (MFMA ceiling, AR fallback, gate saturation, CTC head): for counter runs")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy five times (scale reference for --pmc counters)")
+    ap.add_argument("--mfma-ceiling-only", action="store_true",
+                    help="only run the MFMA-only ceiling kernel (a kernel whose matrix cores never idle: the 100 % mark "
+                         "for the MFMA-busy counters of a --pmc run)")
     args = ap.parse_args()
+    if args.mfma_ceiling_only:
+        from paper_2603_11243_amd.binding import Context
+        wl = WORKLOADS["cfg1_tiny_f32"]
+        ctx = Context(wl.model, make_model_weights(wl.model, wl.seed, device=torch.device("cuda:0")), device=torch.device("cuda:0"))
+        ctx.reserve(max_frames=4096, max_tokens=4096, max_verify_rows=1024, max_utts=8)     # the kernel's 0.5 MB of workspace
+        print(json.dumps(ctx.measure_mfma_ceiling()))
+        return
     if args.copy_reference:
         a = torch.full((1 << 30,), 3, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)

@@ -185,7 +185,7 @@ int attn_tile_rows(int dtype) { return dtype == SSD_BF16 ? 64 : 4; }
 
 struct VerifyPlan {
     size_t row_src, pos, vrow, row_slot, tiles, meta_bytes;     // metadata block, uploaded in one copy
-    size_t x, a, qkv, attn, gu, h, x_c, attn_c, partials, total;   // activations
+    size_t x, a, qkv, attn, gu, h, x_c, attn_c, partials, rope_rows, total;   // activations
 };
 // rows that may go through the few-row GEMM path (split-K scratch): the whole batch, or the
 // verification rows of the last layer
@@ -213,6 +213,9 @@ VerifyPlan plan_verify(const ssd_model_cfg& c, int64_t M, int64_t Mv, int64_t ut
     p.attn_c = o; if (c.dtype == SSD_BF16) o = align_up(o + (size_t)(Mv * dq) * es);
     p.partials = o;
     if (c.dtype == SSD_BF16) o = align_up(o + (size_t)SKINNY_MAX_SPLITS * skinny_rows(M, Mv) * d * 4);
+    // rotary table rows gathered per decoder row once per forward (the positions are the same in every layer)
+    p.rope_rows = o;
+    if (c.dtype == SSD_BF16 && M > SKINNY_MAX_ROWS) o = align_up(o + (size_t)M * 64 * sizeof(float2));
     p.total = o;
     return p;
 }
@@ -747,6 +750,12 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     const int Mi = (int)M, d = m.d_model, dq = m.n_q_heads * m.head_dim, dkv = m.n_kv_heads * m.head_dim;
 
     { ProfScope ps(ctx, SSD_PROF_OTHER); launch_embed_rows(m.dtype, speech_emb, ctx->embed, prompt_ids, draft_ids, d_row_src, Mi, d, m.vocab, x, ctx->dev_flags, st); }
+    float* rope_rows = nullptr;
+    if (m.dtype == SSD_BF16 && M > SKINNY_MAX_ROWS) {
+        ProfScope ps(ctx, SSD_PROF_OTHER);
+        rope_rows = reinterpret_cast<float*>(ws + p.rope_rows);
+        launch_gather_rows(ctx->rope_tab, d_pos, Mi, 64 * sizeof(float2), rope_rows, st);
+    }
     float* partials = reinterpret_cast<float*>(ws + p.partials);
     const int64_t split_stride = (int64_t)Mi * d;
     int pending = 1;            // K splits of the last residual projection still to be added to x (1: none)
@@ -762,7 +771,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
         pending = 1;
         if (m.dtype == SSD_BF16) {
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
-                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, st); }
+                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, rope_rows, st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
             float* xr = x; const void* attr = att; int rows = Mi;
             if (l == m.n_layers - 1) {
@@ -943,7 +952,7 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
                                              m.n_q_heads, m.n_kv_heads, att, st);
                 } else {
                     launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
-                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), st);
+                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), nullptr, st);
                     launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
                 }
                 pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], st);

@@ -39,13 +39,21 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int total, int tiles_
 // Layout16: 16x16 blocks of v_mfma_f32_16x16x32): L::row / L::col give the element a register holds and
 // L::PAIR the distance, in blocks, to the block 32 columns further (where the fused weight layouts put
 // the partner column).
+constexpr int residual_batch(int tm, int g0) {             // largest divisor of tm that is at most g0 (at least 1)
+    int g = 1;
+    for (int c = 1; c <= tm; ++c)
+        if (tm % c == 0 && c <= g0) g = c;
+    return g;
+}
 struct EpiResidual {
     static constexpr bool WANTS_SPLIT = false;
     float* x; int ldx; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
-        constexpr int G0 = 32 / (L::REGS * TN);              // row blocks per batch: about 32 loads in flight
-        constexpr int G = (G0 >= 1 && TM % (G0 >= 1 ? G0 : 1) == 0) ? G0 : 1;
+        // Row blocks per batch: all loads of a batch are in flight together, so a tile pays one memory
+        // latency per batch.  Up to 96 registers of old values (the fragment registers are dead by now).
+        constexpr int G0 = 96 / (L::REGS * TN);
+        constexpr int G = residual_batch(TM, G0);
 #pragma unroll
         for (int i0 = 0; i0 < TM; i0 += G) {
             float old[G][L::REGS][TN];
@@ -77,47 +85,71 @@ struct EpiQkvRope {
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
     const int32_t* row_slot; f16_t* kc; f16_t* vc; int d_q;
+    // optional: the table rows already gathered per decoder row (rope_rows[row][i] = rope_tab[pos[row]][i]),
+    // which takes the position lookup out of the dependency chain
+    const float2* rope_rows;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert((TN * L::BLOCK) % 64 == 0, "rotation partners live 32 packed columns apart in groups of 64");
+        // Column blocks come in groups of 64 packed columns: the first half holds x[i], the second x[i+64]
+        // of 32 rotation pairs (or 64 plain columns of v); block j is handled with its partner j + PAIR.
+        constexpr int NJ = TN / 2;
+        // All table loads of a batch of row blocks are issued before the first store of the batch (the
+        // compiler cannot move a load above a store that might alias it), so a batch costs one memory
+        // latency, not one per block: up to 32 (cos, sin) pairs, 64 registers, are held per lane.
+        constexpr int G = residual_batch(TM, 32 / (NJ * L::REGS) > 0 ? 32 / (NJ * L::REGS) : 1);
+        const float2* tab = rope_rows ? rope_rows : rope_tab;
+        const int d_kv = d_rot - d_q;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            int p_row[L::REGS], slot[L::REGS];
+        for (int i0 = 0; i0 < TM; i0 += G) {
+            int t_row[G][L::REGS], slot[G][L::REGS];
 #pragma unroll
-            for (int r = 0; r < L::REGS; ++r) {
-                const int row = min(row0 + L::row(i, r, lane), M - 1);
-                p_row[r] = pos[row];
-                slot[r] = row_slot ? row_slot[row] : -1;
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if ((j / L::PAIR) % 2 != 0) continue;           // second half of a group of 64: handled with its partner
-                const int p = col0 + j * L::BLOCK;              // packed column of this block
-                const bool rot = p < d_rot;
-                const int head = p / 128, grp = (p % 128) / 64, off = p % 32;
-                const int i_rot = grp * 32 + off + lane % L::BLOCK;
-                const int c0 = rot ? head * 128 + i_rot : p + lane % L::BLOCK;
-                const int c1 = rot ? c0 + 64 : c0 + 32;
-                float2 cs[L::REGS];
-#pragma unroll
-                for (int r = 0; r < L::REGS; ++r) cs[r] = rot ? rope_tab[(int64_t)p_row[r] * 64 + i_rot] : make_float2(1.f, 0.f);
+            for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int r = 0; r < L::REGS; ++r) {
-                    const int row = row0 + L::row(i, r, lane);
-                    if (row >= M) continue;
-                    const float a = acc[i][j][r] * descale, b = acc[i][j + L::PAIR][r] * descale;
-                    f16_t* o = qkv + (int64_t)row * ldq;
-                    const f16_t v0 = f32_to_f16(a * cs[r].x - b * cs[r].y), v1 = f32_to_f16(b * cs[r].x + a * cs[r].y);
-                    o[c0] = v0;
-                    o[c1] = v1;
-                    if (slot[r] >= 0 && c0 >= d_q) {              // a group of 64 lies inside q, k or v
-                        const int d_kv = d_rot - d_q;
-                        f16_t* dst = (rot ? kc : vc) + (int64_t)slot[r] * d_kv - (rot ? d_q : d_rot);
-                        dst[c0] = v0;
-                        dst[c1] = v1;
+                    const int row = min(row0 + L::row(i0 + g, r, lane), M - 1);
+                    t_row[g][r] = rope_rows ? row : pos[row];
+                    slot[g][r] = row_slot ? row_slot[row] : -1;
+                }
+            float2 cs[G][NJ][L::REGS];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int jj = 0; jj < NJ; ++jj) {
+                    const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
+                    const int p = col0 + j * L::BLOCK;
+                    const int i_rot = ((p % 128) / 64) * 32 + p % 32 + lane % L::BLOCK;
+#pragma unroll
+                    for (int r = 0; r < L::REGS; ++r)
+                        cs[g][jj][r] = p < d_rot ? tab[(int64_t)t_row[g][r] * 64 + i_rot] : make_float2(1.f, 0.f);
+                }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int jj = 0; jj < NJ; ++jj) {
+                    const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
+                    const int p = col0 + j * L::BLOCK;              // packed column of this block
+                    const bool rot = p < d_rot;
+                    const int head = p / 128, i_rot = ((p % 128) / 64) * 32 + p % 32 + lane % L::BLOCK;
+                    const int c0 = rot ? head * 128 + i_rot : p + lane % L::BLOCK;
+                    const int c1 = rot ? c0 + 64 : c0 + 32;
+#pragma unroll
+                    for (int r = 0; r < L::REGS; ++r) {
+                        const int row = row0 + L::row(i0 + g, r, lane);
+                        if (row >= M) continue;
+                        const float a = acc[i0 + g][j][r] * descale, b = acc[i0 + g][j + L::PAIR][r] * descale;
+                        const float2 c = cs[g][jj][r];
+                        f16_t* o = qkv + (int64_t)row * ldq;
+                        const f16_t v0 = f32_to_f16(a * c.x - b * c.y), v1 = f32_to_f16(b * c.x + a * c.y);
+                        o[c0] = v0;
+                        o[c1] = v1;
+                        if (slot[g][r] >= 0 && c0 >= d_q) {           // a group of 64 lies inside q, k or v
+                            f16_t* dst = (rot ? kc : vc) + (int64_t)slot[g][r] * d_kv - (rot ? d_q : d_rot);
+                            dst[c0] = v0;
+                            dst[c1] = v1;
+                        }
                     }
                 }
-            }
         }
     }
 };
@@ -321,9 +353,10 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int 
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
-                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st) {
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, hipStream_t st) {
     const int N = d_q + 2 * d_kv;
-    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q};
+    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q,
+                   reinterpret_cast<const float2*>(rope_rows)};
     launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
 }
 

@@ -73,9 +73,10 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 // part into the K/V cache of this layer at that slot (what launch_kv_store does as a separate pass)
 // W_stream (may be NULL): the same weights in the stream layout of launch_stream_layout, read when at
 // most 32 rows are projected
+// rope_rows (may be NULL): rope_tab[pos[row]] gathered per row, [M][64] (cos, sin); read instead of pos and rope_tab
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
-                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, hipStream_t st);
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, hipStream_t st);
 constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
 constexpr int SKINNY_MAX_SPLITS = 8;
 int gemm_residual_splits(int M, int N, int K, bool have_stream);
