@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # plain 1 GiB device copy (`--copy-reference`): FETCH_SIZE reads 524301 for 1048576 KiB (factor 2.0),
 # WRITE_SIZE reads 1048576 (factor 1.0).  See profiles/pmc_traffic_gemm_gate_up_cfg3.md.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_1b_ragged64": (356406.3 * 2.0 + 84095.4 * 1.0) * 1024.0,      # a full layer (5144 rows)
+    "cfg3_1b_ragged64": (354061.6 * 2.0 + 84440.0 * 1.0) * 1024.0,      # a full layer (5144 rows)
 }
 
 
