@@ -46,8 +46,13 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
         for (int j = 0; j < Tile::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] *= descale;
+    // the target ids of a block of rows first: a load inside the row loop would sit behind the stores of the
+    // previous row and cost one memory round trip per row
 #pragma unroll
-    for (int i = 0; i < Tile::TM; ++i)
+    for (int i = 0; i < Tile::TM; ++i) {
+        int tg[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tg[r] = targets[min(row0 + acc_row(i, r, lane), Mv - 1)];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = row0 + acc_row(i, r, lane);
@@ -65,7 +70,7 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
             for (int j = 0; j < Tile::TN; ++j) s += __expf(acc[i][j][r] - m);
             s = row_allreduce32(s, OpSum());
             if (live) {
-                int tgt = targets[row];
+                int tgt = tg[r];
                 tgt = tgt < 0 ? 0 : (tgt >= vocab ? vocab - 1 : tgt);
                 const int rel = tgt - col0 - lane % 32;
                 if (rel >= 0 && rel < Tile::WTN && rel % 32 == 0) {
@@ -86,6 +91,7 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
                 if (live && lane % 32 == 0) part_arg[(int64_t)group * Mv + row] = make_int2(__float_as_int(m), cand);
             }
         }
+    }
 }
 
 template <int BM, int BN, int WM, int WN, int NS>
