@@ -6,7 +6,7 @@
 // is kept.  The full logits (rows x vocab x 4 bytes) never reach memory; what is written is
 // 8 bytes per row per column group.  A second small kernel merges the partials:
 //     logp[r] = logit[r, y_r] - (m + log sum_g s_g exp(m_g - m)).
-#include "gemm_core.h"
+#include "gemm_core16.h"
 #include "ssd_internal.h"
 
 namespace ssd {
@@ -94,6 +94,87 @@ lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm,
     }
 }
 
+// The compute-bound variant (more than 128 rows): 256 x 256 tile on v_mfma_f32_16x16x32_f16 (gemm_core16.h), and a
+// reduction that needs no cross-lane steps.  A wavefront's 128 x 64 slab goes through LDS in two halves of 64
+// rows, written column-major (four consecutive rows of a 16 x 16 accumulator block are one 16-byte store) with a
+// column stride of 68 floats, and read back one row per lane: consecutive lanes read consecutive floats, and every
+// lane scans its 64 logits in registers (maximum, lowest index of the maximum, sum of exponentials).  The
+// row-wise reductions over 32 lanes of the other variants cost ten dependent cross-lane steps per row.
+constexpr int LM16_COL_STRIDE = 68;                               // floats; 16-byte aligned, spreads 16 columns over all banks
+constexpr int LM16_WAVE_FLOATS = 64 * LM16_COL_STRIDE;            // one half slab: 64 columns x 64 rows (+ padding)
+constexpr size_t lmhead16_lds_bytes() {
+    constexpr size_t ring = gemm_lds_bytes<256, 256, 2>(), stage = (size_t)8 * LM16_WAVE_FLOATS * 4;
+    return ring > stage ? ring : stage;
+}
+
+__global__ void __launch_bounds__(512)
+lmhead_mfma16_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,
+                     int Mv, int d, int vocab, float2* __restrict__ part_ms, float* __restrict__ tgt_logit,
+                     int2* __restrict__ part_arg, float descale, int want_greedy) {
+    using Tile = GemmTile16<256, 256, 2, 4>;
+    static_assert(Tile::WTN == LM_WTN && Tile::WTM == 128, "a wavefront owns 128 rows x one column group");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tiles_m = (Mv + 255) / 256;
+    const int v = xcd_contiguous_index(blockIdx.x, gridDim.x);
+    const int tm = v % tiles_m, tn = v / tiles_m;
+    f32x4_t acc[Tile::TM][Tile::TN];
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+    Tile::run(hv, w_lm, Mv, d, tm * 256, tn * 256, 0, d / GEMM_BK, smem_raw, acc);
+    // every wavefront is past the last barrier of the K loop: no fragment read is outstanding, the ring is free
+
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int wm = wave / 4, wn = wave % 4;
+    const int row0 = tm * 256 + wm * 128, col0 = tn * 256 + wn * 64;
+    const int group = col0 / LM_WTN;
+    float* T = reinterpret_cast<float*>(smem_raw) + wave * LM16_WAVE_FLOATS;
+    int tgt[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = targets[min(row0 + 64 * h + lane, Mv - 1)];
+        tgt[h] = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+    }
+    const float k2 = descale * 1.4426950408889634f;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<f32x4_t*>(T + (16 * j + lane % 16) * LM16_COL_STRIDE + 16 * i + 4 * (lane / 16)) = acc[4 * h + i][j];
+        float z[64];
+#pragma unroll
+        for (int c = 0; c < 64; ++c) z[c] = T[c * LM16_COL_STRIDE + lane];
+        float m4[4] = {z[0], z[1], z[2], z[3]};                  // four independent chains
+#pragma unroll
+        for (int c = 4; c < 64; ++c) m4[c % 4] = fmaxf(m4[c % 4], z[c]);
+        const float m = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+        float s4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < 64; ++c) s4[c % 4] += __builtin_amdgcn_exp2f((z[c] - m) * k2);
+        const float ssum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+        const int row = row0 + 64 * h + lane;
+        const float md = m * descale;
+        const int rel = tgt[h] - col0;
+        const bool has_tgt = rel >= 0 && rel < 64;
+        const float zt = T[(has_tgt ? rel : 0) * LM16_COL_STRIDE + lane];
+        if (row < Mv) {
+            part_ms[(int64_t)group * Mv + row] = make_float2(md, ssum);
+            if (has_tgt) tgt_logit[row] = zt * descale;
+        }
+        if (want_greedy) {
+            int arg = 63;
+#pragma unroll
+            for (int c = 62; c >= 0; --c) arg = (z[c] == m) ? c : arg;      // lowest column that holds the maximum
+            if (row < Mv) part_arg[(int64_t)group * Mv + row] = make_int2(__float_as_int(md), col0 + arg);
+        }
+    }
+}
+
 template <int BM, int BN, int WM, int WN, int NS>
 static void launch_lmhead_cfg(const f16_t* hv, const f16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                               float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
@@ -115,14 +196,25 @@ static void launch_lmhead_cfg(const f16_t* hv, const f16_t* w_lm, const int32_t*
 }
 
 // Tile by row count: up to 32 rows the whole job is streaming W_lm once (32 x 256 tile, four-stage
-// ring); up to 128 rows a 128 x 64 tile; otherwise the compute-bound 256 x 256 tile.
+// ring); up to 128 rows a 128 x 64 tile; otherwise the compute-bound 256 x 256 tile (lmhead_mfma16_kernel).
 void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                         float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
                         hipStream_t st) {
     if (Mv <= 0) return;
     if (Mv <= 32) launch_lmhead_cfg<32, 256, 1, 4, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
     else if (Mv <= 128) launch_lmhead_cfg<128, 64, 4, 1, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
-    else launch_lmhead_cfg<256, 256, 2, 4, 2>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    else {
+        constexpr size_t lds = lmhead16_lds_bytes();
+        static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_mfma16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            attr_set = true;
+        }
+        const int tiles = ((Mv + 255) / 256) * (vocab / 256);
+        hipLaunchKernelGGL(lmhead_mfma16_kernel, dim3(tiles), dim3(512), lds, st, (const f16_t*)hv, (const f16_t*)w_lm, targets,
+                           Mv, d, vocab, part_ms, tgt_logit, part_arg, descale, want_greedy ? 1 : 0);
+    }
 }
 
 // One wavefront per row merges the per-group partials.
