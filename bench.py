@@ -427,6 +427,22 @@ def main():
     per_gemm_flops = {"gemm_qkv": 2.0 * L * M * qkv_params, "gemm_o": 2.0 * L * rows_avg * m.d_model * m.d_q,
                       "gemm_gate_up": 2.0 * L * rows_avg * m.d_model * 2 * m.d_ff, "gemm_down": 2.0 * L * rows_avg * m.d_model * m.d_ff}
     out["projection_tflops"] = {k: (f / (breakdown[k] * 1e-3) / 1e12 if breakdown.get(k) else None) for k, f in per_gemm_flops.items()}
+    # accept_prefix: LM head fused with the log-softmax and the gather (+ finalize and prefix scan), HIP-event time
+    # of the class in the breakdown step.  MFMA bound above about 310 rows, weight streaming below.
+    if breakdown.get("lmhead_accept"):
+        t_acc = breakdown["lmhead_accept"] * 1e-3
+        acc_flops = 2.0 * Mv * m.vocab * m.d_model
+        acc_bytes = 2.0 * (m.vocab * m.d_model + Mv * m.d_model) + 4.0 * Mv
+        if Mv > 310:
+            out["accept_roofline"] = {"bound": "mfma", "achieved": acc_flops / t_acc / 1e12, "peak": PEAK_MFMA_TFLOPS,
+                                      "unit": "TFLOP/s", "frac": acc_flops / t_acc / 1e12 / PEAK_MFMA_TFLOPS,
+                                      "rows": Mv, "ms": breakdown["lmhead_accept"],
+                                      "logit_bytes_never_written": 4.0 * Mv * m.vocab}
+        else:
+            out["accept_roofline"] = {"bound": "hbm", "achieved": acc_bytes / t_acc / 1e9, "peak": PEAK_HBM_GBS,
+                                      "unit": "GB/s", "frac": acc_bytes / t_acc / 1e9 / PEAK_HBM_GBS,
+                                      "rows": Mv, "ms": breakdown["lmhead_accept"],
+                                      "logit_bytes_never_written": 4.0 * Mv * m.vocab}
     if not args.main_only:
         tf, ghz = ctx.measure_mfma_ceiling(20000)
         out["mfma_ceiling_this_device"] = {"tflops": tf, "shader_ghz": ghz, "frac_of_nominal_peak": tf / PEAK_MFMA_TFLOPS,

@@ -140,18 +140,41 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
         if (kb + ATT_KB < kv_end) load_kv(kb + ATT_KB);
         __syncthreads();
         if (wave_live && kb <= q_first + 31) {
-            // ---- S^T for the two 32-key halves of the block
+            // ---- S^T for the two 32-key halves of the block.  The K fragments are read four MFMAs ahead (a read
+            // issued right before its MFMA leaves the LDS latency exposed 32 times per block).
             f32x16_t s_acc[2];
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s_acc[c][r] = 0.f;
-                const f16_t* kf = Ks + (c * 32 + lcol) * ATT_K_STRIDE + hgrp * 8;
+            const f16_t* kf0 = Ks + lcol * ATT_K_STRIDE + hgrp * 8;
+            auto k_frag = [&](int idx) {      // idx = 8 * half + kk
+                return as_f16x8(*reinterpret_cast<const uint4*>(kf0 + (idx / 8) * 32 * ATT_K_STRIDE + (idx % 8) * 16));
+            };
+            f16x8_t kq[4];
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
-                    s_acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        as_f16x8(*reinterpret_cast<const uint4*>(kf + kk * 16)), qf[kk], s_acc[c], 0, 0, 0);
+            for (int p = 0; p < 4; ++p) kq[p] = k_frag(p);
+#pragma unroll
+            for (int idx = 0; idx < 16; ++idx) {
+                s_acc[idx / 8] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kq[idx % 4], qf[idx % 8], s_acc[idx / 8], 0, 0, 0);
+                if (idx + 4 < 16) kq[idx % 4] = k_frag(idx + 4);
             }
+            // pin the order (the scheduler would sink every read to just before its MFMA)
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int idx = 0; idx < 16; ++idx) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (idx + 4 < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            // first V^T fragments: their latency hides behind the softmax arithmetic
+            const f16_t* vf0 = Vt + lcol * ATT_V_STRIDE + hgrp * 8;
+            auto v_frag = [&](int idx) {      // idx = 4 * db + ks
+                return as_f16x8(*reinterpret_cast<const uint4*>(vf0 + (idx / 4) * 32 * ATT_V_STRIDE + (idx % 4) * 16));
+            };
+            f16x8_t vq[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) vq[p] = v_frag(p);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             // ---- causal mask (only blocks that reach past the first query of the wavefront)
             if (kb + ATT_KB - 1 > q_first) {
 #pragma unroll
@@ -197,12 +220,14 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
                 for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
             // ---- O^T += V^T . P^T
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const f16_t* vf = Vt + (db * 32 + lcol) * ATT_V_STRIDE + hgrp * 8;
+            for (int idx = 0; idx < 16; ++idx) {
+                o_acc[idx / 4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vq[idx % 4], pf[idx % 4], o_acc[idx / 4], 0, 0, 0);
+                if (idx + 4 < 16) vq[idx % 4] = v_frag(idx + 4);
+            }
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        as_f16x8(*reinterpret_cast<const uint4*>(vf + ks * 16)), pf[ks], o_acc[db], 0, 0, 0);
+            for (int idx = 0; idx < 16; ++idx) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (idx + 4 < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
         }
         __syncthreads();
