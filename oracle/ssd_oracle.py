@@ -209,6 +209,15 @@ def assemble_inputs(weights: Dict, speech_emb, cu_speech, prompt_ids, cu_prompt,
     return xs
 
 
+def lm_head_logp(h: np.ndarray, w_lm: np.ndarray, target: int):
+    """Eq. 5 at one scoring position: log-softmax over the whole vocabulary of the logits w_lm @ h, read at
+    the target id; also the greedy token (lowest-index argmax).  h: final-normed hidden row."""
+    logits = w_lm @ h
+    mx = logits.max()
+    lse = mx + math.log(np.exp(logits - mx).sum())
+    return float(logits[target] - lse), int(np.argmax(logits))
+
+
 def draft_logp(weights: Dict, cfg, speech_emb, cu_speech, prompt_ids, cu_prompt,
                draft_ids, cu_draft, return_hidden: bool = False, return_greedy: bool = False):
     """log p(y_i | y_<i, g) for every draft token (the quantity thresholded in Eq. 5, Sec. 2.2).
@@ -235,12 +244,8 @@ def draft_logp(weights: Dict, cfg, speech_emb, cu_speech, prompt_ids, cu_prompt,
             if S + P + i - 2 < 0:
                 raise ValueError("first draft token has no conditioning position")
             h = rmsnorm(x[S + P + i - 2], w_f, cfg.rms_eps)
-            logits = w_lm @ h
-            mx = logits.max()
-            lse = mx + math.log(np.exp(logits - mx).sum())
-            lp[i - 1] = logits[y[i - 1]] - lse
+            lp[i - 1], gt[i - 1] = lm_head_logp(h, w_lm, int(y[i - 1]))
             hv[i - 1] = h
-            gt[i - 1] = int(np.argmax(logits))
         out.append(lp)
         hid.append(hv)
         greedy.append(gt)

@@ -215,6 +215,44 @@ def test_bf16_row_counts_around_tile_and_split_thresholds(M):
     assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a dropped tile would be O(1)
 
 
+@pytest.mark.parametrize("Mv", [129, 192, 193, 256, 257, 385])
+def test_accept_prefix_alone_row_counts_around_lm_head_tiles(Mv):
+    """accept_prefix on given hidden rows (no decoder forward): verification-row counts on and next to the
+    boundaries of the LM head's 256-row tile and of the 64-row halves in which a wavefront reduces its slab;
+    likelihoods, greedy tokens (lowest index on ties) and prefix lengths against the oracle's Eq. 5."""
+    from paper_2603_11243_amd.binding import Context
+    wl = scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=1, B=3)
+    w = make_model_weights(wl.model, 777, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(Mv)
+    # unit-RMS rows, as after the final norm; the library hands hidden rows over as IEEE half
+    h = torch.randn(Mv, wl.model.d_model, generator=g, device="cuda").to(torch.float16)
+    rng = np.random.default_rng(Mv)
+    U = [Mv // 3, 0, Mv - Mv // 3]                      # an utterance without a draft in the middle
+    cu_d = np.concatenate([[0], np.cumsum(U)]).astype(np.int32)
+    y = rng.integers(0, wl.model.vocab, Mv).astype(np.int32)
+    y[0], y[-1] = 0, wl.model.vocab - 1                 # first and last column of the vocabulary
+    tau = _tau_for(wl)
+    ctx = Context(wl.model, w)
+    ctx.reserve(max_tokens=Mv + 8, max_verify_rows=Mv, max_utts=3)
+    out = ctx.accept_prefix(h, _dev(y), cu_d, tau, want_greedy=True)
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    ctx.close()
+    tol = TOL_LOGP[wl.model.dtype]
+    w_lm = w["lm_head"].double().cpu().numpy()
+    h64 = h.double().cpu().numpy()
+    lp = np.zeros(Mv)
+    for i in range(Mv):
+        lp[i], gt = O.lm_head_logp(h64[i], w_lm, int(y[i]))
+        assert abs(res["draft_logp"][i] - lp[i]) <= tol, f"row {i}: {res['draft_logp'][i]} vs {lp[i]}"
+        if res["greedy_tok"][i] != gt:                  # only legal when the two logits are within tolerance
+            logits = w_lm @ h64[i]
+            assert logits.max() - logits[res["greedy_tok"][i]] <= tol
+    assert np.abs(res["draft_logp"] - lp).max() < 5e-3   # one matrix product: far inside the budget
+    for b in range(3):
+        check_accept_len(res["accept_len"][b], res["all_accepted"][b], lp[cu_d[b]:cu_d[b + 1]], tau, tol)
+
+
 def test_bf16_empty_drafts_and_single_row_utterances():
     """bf16 path, two 1B-width layers: utterances without a draft inside a batch (vacuous acceptance), an
     utterance made of one speech row, and a batch in which nobody has a draft (nothing to score)."""
