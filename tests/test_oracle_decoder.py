@@ -200,6 +200,33 @@ def test_lm_head_normalisation_and_gather():
         assert abs(lp2[0][i] - want) < 1e-12
 
 
+def test_lm_head_logp_closed_forms():
+    """The Eq. 5 step at one position, on its own: cases with a known answer."""
+    V, d = 37, 8
+    h = np.arange(1, d + 1, dtype=np.float64)
+    # all-zero head: the uniform distribution, and the lowest index wins the tie
+    lp, g = O.lm_head_logp(h, np.zeros((V, d)), 5)
+    assert abs(lp + math.log(V)) < 1e-12 and g == 0
+    # one row scaled so that its logit is L, all other logits 0: p = e^L / (e^L + V - 1)
+    W = np.zeros((V, d)); W[11] = h / (h @ h) * 3.0
+    lp, g = O.lm_head_logp(h, W, 11)
+    assert abs(lp - (3.0 - math.log(math.exp(3.0) + V - 1))) < 1e-12 and g == 11
+    lp_other, _ = O.lm_head_logp(h, W, 4)
+    assert abs(lp_other - (0.0 - math.log(math.exp(3.0) + V - 1))) < 1e-12
+    # shifting every logit by a constant (a bias direction in h) changes nothing; huge logits do not overflow
+    rng = np.random.default_rng(0)
+    W = rng.normal(size=(V, d))
+    base = [O.lm_head_logp(h, W, t)[0] for t in range(V)]
+    assert abs(sum(math.exp(x) for x in base) - 1) < 1e-12
+    big = [O.lm_head_logp(h * 1e3, W, t)[0] for t in range(V)]
+    assert all(np.isfinite(big)) and abs(max(big)) < 1e-9          # one token takes all the mass
+    # two equal maxima: the lowest index is the greedy token
+    W2 = W.copy(); W2[20] = W2[3]
+    top = int(np.argmax(W2 @ h))
+    if top in (3, 20):
+        assert O.lm_head_logp(h, W2, 0)[1] == 3
+
+
 def test_ar_fallback_is_consistent_with_teacher_forced_scoring():
     """Feeding the generated tokens back as a draft: the greedy token at every scoring position is the
     token that was generated there (ties aside, none here), and the first token is the greedy choice
