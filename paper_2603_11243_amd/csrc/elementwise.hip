@@ -103,6 +103,15 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
             }
         }
     }
+    // the gain is fetched before the reduction, so that its cache round trip overlaps with it
+    uint2 g16[sizeof(T) == 2 ? NV : 1];
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = lane + 64 * j;
+            g16[j] = i < n4 ? reinterpret_cast<const uint2*>(gain)[i] : make_uint2(0u, 0u);
+        }
+    }
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < NV; ++j) ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
@@ -114,7 +123,7 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
         const int i = lane + 64 * j;
         if (i >= n4) continue;
         if constexpr (sizeof(T) == 2) {
-            const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
+            const uint2 g = g16[j];
             uint2 o;
             o.x = pack_f16x2(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x));
             o.y = pack_f16x2(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y));
@@ -142,6 +151,15 @@ __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x,
     const int n4 = d / 4;
     float4 v[MAXV];
     float ss = 0.f;
+    // the gain is fetched up front: its cache round trip overlaps with the row loads and the reduction
+    uint2 g16[sizeof(T) == 2 ? MAXV : 1];
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (int k = 0; k < MAXV; ++k) {
+            const int i = threadIdx.x + k * 256;
+            g16[k] = i < n4 ? reinterpret_cast<const uint2*>(gain)[i] : make_uint2(0u, 0u);
+        }
+    }
 #pragma unroll
     for (int k = 0; k < MAXV; ++k) {
         const int i = threadIdx.x + k * 256;
@@ -170,7 +188,7 @@ __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x,
         const int i = threadIdx.x + k * 256;
         if (i >= n4) continue;
         if constexpr (sizeof(T) == 2) {
-            const uint2 g = reinterpret_cast<const uint2*>(gain)[i];
+            const uint2 g = g16[k];
             uint2 o;
             o.x = pack_f16x2(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x));
             o.y = pack_f16x2(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y));
