@@ -94,3 +94,18 @@ def test_plan_batches_matches_oracle(lib):
     assert lib.ssd_plan_batches(None, 3, 10, 0, None, None, C.byref(h)) == -1
     bad = np.array([3, 0, 2], dtype=np.int32); o = np.empty(3, np.int32); s = np.empty(4, np.int32)
     assert lib.ssd_plan_batches(bad.ctypes.data, 3, 10, 0, o.ctypes.data, s.ctypes.data, C.byref(h)) == -1
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
+    """bench.py is a one-GPU measurement of the HIP path: --gpus 2 exits with a message that says so, and
+    on a machine without a GPU it stops instead of timing anything else."""
+    import os
+    import subprocess
+    import sys
+    bench = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, bench, "--steps", "1"], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 1 and "no CPU fallback" in r.stderr and r.stdout.strip() == ""
