@@ -173,18 +173,22 @@ __device__ __forceinline__ void sum_splits8(const DecodeFused& f, int64_t row_of
         }
     }
 }
-// dims 8 dc .. 8 dc + 7 of rotated head `head_col0` (packed column of the head's first dim) at position p
-__device__ __forceinline__ void rotated_chunk(const DecodeFused& f, int64_t row_off, int head_col0, int dc, int p, float (&v)[8]) {
+// the eight (cos, sin) pairs a lane needs at position p: dims (dc % 8) * 8 .. + 7 of the first half of a head
+__device__ __forceinline__ void rope_entries(const DecodeFused& f, int dc, int p, float2 (&cs)[8]) {
+    const int i0 = (dc % 8) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[e] = f.rope_tab[(int64_t)p * 64 + i0 + e];
+}
+// dims 8 dc .. 8 dc + 7 of rotated head `head_col0` (packed column of the head's first dim); cs from rope_entries,
+// requested before the partial sums so that its round trip overlaps theirs
+__device__ __forceinline__ void rotated_chunk(const DecodeFused& f, int64_t row_off, int head_col0, int dc, const float2 (&cs)[8], float (&v)[8]) {
     const int i0 = (dc % 8) * 8;                              // dim inside the first half of the head
     const int col_lo = head_col0 + (i0 / 32) * 64 + (i0 % 32);
     float lo[8], hi[8];
     sum_splits8(f, row_off, col_lo, lo);
     sum_splits8(f, row_off, col_lo + 32, hi);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float2 cs = f.rope_tab[(int64_t)p * 64 + i0 + e];
-        v[e] = dc < 8 ? lo[e] * cs.x - hi[e] * cs.y : hi[e] * cs.x + lo[e] * cs.y;
-    }
+    for (int e = 0; e < 8; ++e) v[e] = dc < 8 ? lo[e] * cs[e].x - hi[e] * cs[e].y : hi[e] * cs[e].x + lo[e] * cs[e].y;
 }
 
 template <bool FUSED>
@@ -231,12 +235,14 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[e] = 0.f;
         if (kg == 0) {
-            rotated_chunk(fu, row_off, h * HD, dc, p, qf);
+            float2 cs[8];                                    // the same entries rotate q and the new k
+            rope_entries(fu, dc, p, cs);
+            rotated_chunk(fu, row_off, h * HD, dc, cs, qf);
 #pragma unroll
             for (int e = 0; e < 8; ++e) qf[e] = (float)(_Float16)qf[e] * sc;      // q is rounded like a stored row
             if (wave == 0) {
                 float kn[8], vn[8];
-                rotated_chunk(fu, row_off, d_q + kvh * HD, dc, p, kn);
+                rotated_chunk(fu, row_off, d_q + kvh * HD, dc, cs, kn);
                 sum_splits8(fu, row_off, d_q + d_kv + kvh * HD + dc * 8, vn);
                 // the cache holds half precision: the new row takes part in this step with the values later steps read
                 uint4 kw;
