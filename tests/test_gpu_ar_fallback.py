@@ -44,13 +44,18 @@ def _run_chain(wl, w, vi, tau, n_steps):
     return acc_len, rej, first, toks, acc["draft_logp"].cpu().numpy()
 
 
-def _check_against_oracle(wl, w, vi, tau, n_steps, acc_len, rej, first, toks, logp_gpu):
+def _check_against_oracle(wl, w, vi, tau, n_steps, acc_len, rej, first, toks, logp_gpu, sample=None):
+    """sample: positions in `rej` to check (default: every rejected utterance)."""
+    from tests.test_gpu_verify import _subset
     tol = TOL_LOGP[wl.model.dtype]
-    lp = O.draft_logp(w, wl.model, vi.speech_emb, vi.cu_speech, vi.prompt_ids, vi.cu_prompt, vi.draft_ids, vi.cu_draft)
+    ks = list(range(len(rej))) if sample is None else list(sample)
+    sub = _subset(vi, [int(rej[k]) for k in ks])
+    lp_sub = O.draft_logp(w, wl.model, sub.speech_emb, sub.cu_speech, sub.prompt_ids, sub.cu_prompt, sub.draft_ids, sub.cu_draft)
     w_lm = w["lm_head"].double().cpu().numpy()
     n_exact = 0
-    for k, b in enumerate(rej):
-        check_accept_len(acc_len[b], False, lp[b], tau, tol)
+    for j, k in enumerate(ks):
+        b = rej[k]
+        check_accept_len(acc_len[b], False, lp_sub[j], tau, tol)
         sp = vi.speech_emb[vi.cu_speech[b]:vi.cu_speech[b + 1]]
         pr = vi.prompt_ids[vi.cu_prompt[b]:vi.cu_prompt[b + 1]]
         prefix = vi.draft_ids[vi.cu_draft[b]:vi.cu_draft[b] + acc_len[b]]
@@ -124,3 +129,23 @@ def test_ar_fallback_bf16_reduced_depth(name, layers, B, n_steps):
     n_exact = _check_against_oracle(wl, w, vi, tau, n_steps, *res)
     print(f"{wl.name}: {n_exact} of {(n_steps + 1) * len(res[1])} generated tokens identical to the oracle's")
     assert n_exact >= (n_steps + 1) * len(res[1]) // 2
+
+
+def test_ar_fallback_bf16_full_size_sampled_utterances():
+    """The configuration bench.py times (ragged batch of 64 on the full 24-layer 1B-class decoder): the whole chain on
+    the GPU, the oracle's continuation for the two shortest rejected utterances."""
+    wl = WORKLOADS["cfg3_1b_ragged64"]
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, wl.seed, device="cuda")
+    tau = _tau_for(wl)
+    n_steps = 2
+    res = _run_chain(wl, w, vi, tau, n_steps)
+    rej = res[1]
+    assert 1 <= len(rej) <= 32                     # the few-row path of the step, as in the benchmark
+    n = np.diff(vi.cu_speech) + np.diff(vi.cu_prompt) + np.diff(vi.cu_draft)
+    sample = np.argsort(n[rej])[:2]
+    n_exact = _check_against_oracle(wl, w, vi, tau, n_steps, *res, sample=sample)
+    print(f"{wl.name}: {n_exact} of {(n_steps + 1) * len(sample)} generated tokens identical to the oracle's")
+    assert n_exact >= (n_steps + 1) * len(sample) // 2
