@@ -157,6 +157,29 @@ int ctc_gate(ssd_ctx *ctx, const void *logits, int dtype, const int32_t *cu_fram
              float *max_entropy /*dev [B]*/, uint8_t *gate_pass /*dev [B]*/,
              int32_t *draft_ctc /*dev [cu_frames[B]]*/, int32_t *draft_len /*dev [B]*/);
 
+/* ctc_gate for callers that cannot allocate: code under HIP graph capture, tight serving loops and
+ * harnesses that forbid allocation.  Needs no context and no workspace; calls no hipMalloc, hipFree,
+ * host allocation, copy or wait: it only launches the two kernels of ctc_gate on `hip_stream`
+ * (a hipStream_t, NULL = default stream) of the current device.  The per-frame entropies and greedy
+ * labels, which ctc_gate keeps in the workspace, live in a device array built into the library:
+ * 8 bytes per frame, SSD_NOALLOC_MAX_FRAMES frames (2 MiB), one copy per GPU for the life of the process.
+ * Differences from ctc_gate: cu_frames_dev is a DEVICE array of B+1 prefix sums (the host cannot check
+ * it: the kernels clamp every utterance's frame range into [0, n_frames], so a malformed array gives
+ * wrong results for that utterance but no access outside the buffers); n_frames (= cu_frames_dev[B]) is
+ * passed explicitly; frame_entropy / frame_argmax are not returned.  Outputs as for ctc_gate and, for
+ * well-formed prefix sums, bit-identical to it.
+ * Errors (nothing is launched): SSD_EINVAL (NULL pointer, B, n_frames or V_ctc <= 0, blank_id out of
+ * range), SSD_EUNSUPPORTED (dtype), SSD_ESHAPE (n_frames > SSD_NOALLOC_MAX_FRAMES), SSD_EHIP.  `err`
+ * (host, may be NULL) receives a message of at most err_len bytes.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or host threads) race; calls on one stream are ordered and safe. */
+#define SSD_NOALLOC_MAX_FRAMES 262144
+int ctc_gate_noalloc(void *hip_stream, const void *logits /*dev [n_frames, V_ctc]*/, int dtype,
+                     const int32_t *cu_frames_dev /*dev [B+1]*/, int B, int64_t n_frames, int V_ctc, int blank_id,
+                     float tau_ctc, float *max_entropy /*dev [B]*/, uint8_t *gate_pass /*dev [B]*/,
+                     int32_t *draft_ctc /*dev [n_frames]*/, int32_t *draft_len /*dev [B]*/,
+                     char *err /*host*/, size_t err_len);
+
 /* Sec. 3.1 (output layer of the CTC encoder: 1024-wide states, 348 symbols) feeding Sec. 2.1.
  * ssd_set_ctc_head copies the output layer into the context (padded to a multiple of 128
  * symbols; the caller's arrays may be released on return; a second call replaces the first).

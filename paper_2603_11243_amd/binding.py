@@ -20,7 +20,8 @@ _STATUS = {0: "SSD_OK", -1: "SSD_EINVAL", -2: "SSD_ESHAPE", -3: "SSD_EWORKSPACE"
 EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspace", "ssd_last_error",
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ssd_measure_hbm_read", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
-           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags"]
+           "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags",
+           "ctc_gate_noalloc"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
@@ -99,6 +100,8 @@ def load_library() -> C.CDLL:
     lib.ssd_set_ctc_head.restype = i32
     lib.ctc_head_gate.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.ctc_head_gate.restype = i32
+    lib.ctc_gate_noalloc.argtypes = [vp, vp, i32, vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, C.c_char_p, C.c_size_t]
+    lib.ctc_gate_noalloc.restype = i32
     return lib
 
 
@@ -342,6 +345,25 @@ class Context:
                                             _ptr(out["draft_logp"]), _ptr(out["accept_len"]),
                                             _ptr(out["all_accepted"]), _ptr(out.get("greedy_tok"))))
         return out
+
+
+NOALLOC_MAX_FRAMES = 262144
+
+
+def ctc_gate_noalloc(logits: torch.Tensor, cu_frames_dev: torch.Tensor, blank_id: int, tau_ctc: float, out: dict,
+                     stream=None) -> dict:
+    """ctc_gate_noalloc: every buffer is the caller's (`out` holds max_entropy, gate_pass, draft_ctc, draft_len;
+    cu_frames_dev is an int32 device tensor of B+1 prefix sums); the call itself allocates nothing."""
+    st = stream if stream is not None else torch.cuda.current_stream(logits.device)
+    B, n_frames, V = int(cu_frames_dev.numel()) - 1, int(logits.shape[0]), int(logits.shape[1])
+    assert cu_frames_dev.dtype == torch.int32
+    err = C.create_string_buffer(256)
+    rc = lib().ctc_gate_noalloc(C.c_void_p(st.cuda_stream), _ptr(logits), _DTYPE_CODE[logits.dtype], _ptr(cu_frames_dev), B,
+                                n_frames, V, blank_id, tau_ctc, _ptr(out["max_entropy"]), _ptr(out["gate_pass"]),
+                                _ptr(out["draft_ctc"]), _ptr(out["draft_len"]), err, len(err))
+    if rc != 0:
+        raise SsdError(rc, err.value.decode())
+    return out
 
 
 def plan_batches(lengths, max_tokens: int, padded: bool = False):

@@ -664,7 +664,7 @@ int ctc_head_gate(ssd_ctx* ctx, const void* enc_h, const int32_t* cu_frames, int
             launch_ctc_head(static_cast<const uint16_t*>(enc_h) + r0 * d, ctx->head_w, ctx->head_bias, rows, d, V,
                             ctx->head_V_pad, reinterpret_cast<float4*>(ws + p.part), H + r0, arg + r0, ctx->stream);
         }
-        launch_gate_utterances(H, arg, cu_dev, B, blank_id, tau_ctc, max_entropy, gate_pass, draft_ctc, draft_len,
+        launch_gate_utterances(H, arg, cu_dev, n_rows, B, blank_id, tau_ctc, max_entropy, gate_pass, draft_ctc, draft_len,
                                ctx->stream);
     }
     HIP_TRY(ctx, hipGetLastError());

@@ -305,17 +305,18 @@ __global__ void __launch_bounds__(256) gate_frames_generic(const T* __restrict__
     }
 }
 
-// One workgroup (256 threads) per utterance.
+// One workgroup (256 threads) per utterance.  The frame range of an utterance is clamped into
+// [0, n_rows], so that prefix sums that were never seen by the host cannot lead outside H / arg / draft.
 __global__ void __launch_bounds__(256) gate_utterances(const float* __restrict__ H,
                                                        const int32_t* __restrict__ arg,
-                                                       const int32_t* __restrict__ cu_frames, int blank,
+                                                       const int32_t* __restrict__ cu_frames, int n_rows, int blank,
                                                        float tau, float* __restrict__ max_entropy,
                                                        uint8_t* __restrict__ gate_pass,
                                                        int32_t* __restrict__ draft, int32_t* __restrict__ draft_len) {
     __shared__ int wave_cnt[4];
     __shared__ float wave_max[4];
     const int b = blockIdx.x;
-    const int lo = cu_frames[b], hi = cu_frames[b + 1];
+    const int lo = min(max(cu_frames[b], 0), n_rows), hi = min(max(cu_frames[b + 1], lo), n_rows);
     const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
     float mx = -INFINITY;
     int written = 0;                                   // same value in every thread
@@ -354,10 +355,10 @@ __global__ void __launch_bounds__(256) gate_utterances(const float* __restrict__
     }
 }
 
-void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int B, int blank,
+void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int64_t n_rows, int B, int blank,
                             float tau, float* max_entropy, uint8_t* gate_pass, int32_t* draft, int32_t* draft_len,
                             hipStream_t st) {
-    hipLaunchKernelGGL(gate_utterances, dim3(B), dim3(256), 0, st, H, arg, cu_frames_dev, blank, tau,
+    hipLaunchKernelGGL(gate_utterances, dim3(B), dim3(256), 0, st, H, arg, cu_frames_dev, (int)n_rows, blank, tau,
                        max_entropy, gate_pass, draft, draft_len);
 }
 
@@ -407,7 +408,7 @@ void launch_gate(const void* logits, int dtype, int64_t n_rows, int V, const int
                  int32_t* draft, int32_t* draft_len, hipStream_t st) {
     if (dtype == SSD_BF16) launch_frames<bf16_t>(static_cast<const bf16_t*>(logits), n_rows, V, H, arg, st);
     else launch_frames<float>(static_cast<const float*>(logits), n_rows, V, H, arg, st);
-    launch_gate_utterances(H, arg, cu_frames_dev, B, blank, tau, max_entropy, gate_pass, draft, draft_len, st);
+    launch_gate_utterances(H, arg, cu_frames_dev, n_rows, B, blank, tau, max_entropy, gate_pass, draft, draft_len, st);
 }
 
 }  // namespace ssd

@@ -16,7 +16,8 @@ void launch_gate(const void* logits, int dtype, int64_t n_rows, int V, const int
                  int32_t* draft, int32_t* draft_len, hipStream_t st);
 
 // second half of the gate on its own: per-utterance max entropy, threshold test and collapse
-void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int B, int blank,
+// (frame ranges are clamped into [0, n_rows] on the device)
+void launch_gate_utterances(const float* H, const int32_t* arg, const int32_t* cu_frames_dev, int64_t n_rows, int B, int blank,
                             float tau, float* max_entropy, uint8_t* gate_pass, int32_t* draft, int32_t* draft_len,
                             hipStream_t st);
 

@@ -109,3 +109,23 @@ def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
     if not torch.cuda.is_available():
         r = subprocess.run([sys.executable, bench, "--steps", "1"], capture_output=True, text=True, timeout=300)
         assert r.returncode == 1 and "no CPU fallback" in r.stderr and r.stdout.strip() == ""
+
+
+def test_noalloc_gate_rejects_bad_arguments_on_the_host(lib):
+    """ctc_gate_noalloc: argument and size errors come back before anything touches a device."""
+    fake = C.c_void_p(0x1000)
+    err = C.create_string_buffer(200)
+    call = lambda **k: lib.ctc_gate_noalloc(None, k.get("logits", fake), k.get("dtype", 1), fake, k.get("B", 2),
+                                            k.get("n", 100), k.get("V", 16), k.get("blank", 0), C.c_float(0.7),
+                                            fake, fake, fake, fake, err, len(err))
+    assert call(logits=None) == -1
+    assert call(B=0) == -1
+    assert call(n=0) == -1
+    assert call(V=0) == -1
+    assert call(blank=16) == -1
+    assert call(dtype=9) == -5
+    from paper_2603_11243_amd import binding
+    assert call(n=binding.NOALLOC_MAX_FRAMES + 1) == -2
+    assert b"at most 262144" in err.value
+    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    assert re.search(r"#define\s+SSD_NOALLOC_MAX_FRAMES\s+(\d+)", text).group(1) == str(binding.NOALLOC_MAX_FRAMES)
