@@ -89,6 +89,12 @@ typedef struct {
  * norm gains (and for SSD_F32 wo, w_down, lm_head) are read in place on every call. */
 int ssd_create(ssd_ctx **out, const ssd_model_cfg *cfg, const ssd_weights *weights, void *hip_stream);
 void ssd_destroy(ssd_ctx *ctx);
+/* SSD_BF16 models: number of weight values (all projection matrices and lm_head) whose conversion to
+ * half times the tensor's power of two was not exact.  A bf16 value keeps all of its 8 significant
+ * bits when its magnitude is within 31 binades of the largest magnitude of its tensor; smaller ones are
+ * rounded to the half subnormal grid (absolute error below 2^-39 of the tensor's largest magnitude).
+ * 0 for SSD_F32 models and for every tensor drawn from a distribution of ordinary dynamic range. */
+int64_t ssd_inexact_weights(const ssd_ctx *ctx);
 
 /* Bytes of workspace needed for calls with at most max_frames CTC frames, max_tokens decoder rows
  * (sum over utterances of speech + prompt + draft), max_verify_rows draft tokens and max_utts
@@ -104,8 +110,13 @@ const char *ssd_last_error(const ssd_ctx *ctx);
 /* Conditions that only the device sees (they depend on data in device memory) do not fail a call: the
  * kernels repair them and raise a sticky flag.  ssd_device_flags waits for the stream, writes the flags
  * raised since the last call to *flags (host) and clears them.
- *   SSD_FLAG_TOKEN_CLAMPED  a prompt, draft or first_tok id outside [0, vocab) was clamped into range */
-enum ssd_device_flag { SSD_FLAG_TOKEN_CLAMPED = 1 };
+ *   SSD_FLAG_TOKEN_CLAMPED  a prompt, draft or first_tok id outside [0, vocab) was clamped into range
+ *   SSD_FLAG_ACT_OVERFLOW   SSD_BF16 models: an activation left the range of the matrix-core operand type
+ *                           (|v| > 65504 for IEEE half, or NaN) at one of the points where the fp32 pipeline
+ *                           rounds to it (RMSNorm output, rotated q / k and v, SiLU(gate)*up, K/V-cache rows) and
+ *                           was stored saturated to +-65504, or a log-likelihood came out non-finite.  Results of
+ *                           calls since the last read are then not the model's: re-run in fp32 or rescale. */
+enum ssd_device_flag { SSD_FLAG_TOKEN_CLAMPED = 1, SSD_FLAG_ACT_OVERFLOW = 2 };
 int ssd_device_flags(ssd_ctx *ctx, int32_t *flags /*host*/);
 
 /* Measurement aid (no counterpart in the paper): times kernel launches with HIP events recorded on
@@ -197,6 +208,33 @@ int ctc_head_gate(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*ho
                   float tau_ctc, float *frame_entropy, int32_t *frame_argmax, float *max_entropy,
                   uint8_t *gate_pass, int32_t *draft_ctc, int32_t *draft_len);
 
+/* Between Sec. 2.1 and Sec. 2.2 (Eq. 7: only utterances that fail the entropy gate are verified).  Packs the
+ * verification inputs of the n_sel selected utterances (sel: host, indices into the batch of B utterances, in
+ * the order they will be verified) on the device:
+ *   speech_out  [sum S, d_model]  rows of speech_all (dev [cu_speech_all[B], d_model], dtype SSD_F32 / SSD_BF16)
+ *   prompt_out  [sum P]           entries of prompt_all (dev)
+ *   draft_ids_out [sum U]         ctc_to_llm[draft_ctc[cu_frames[b] + i]], i < draft_len[b]: the draft of ctc_gate
+ *                                 re-expressed in LLM token ids through a caller-supplied table (dev [V_ctc]; the
+ *                                 paper leaves re-tokenisation to its software stack; NULL copies the ids unchanged)
+ * and writes the matching prefix sums cu_speech_out / cu_prompt_out / cu_draft_out (host [n_sel + 1]) that
+ * verify_forward and accept_prefix take.  cu_frames, draft_len (host copy of ctc_gate's output), cu_speech_all and
+ * cu_prompt_all are host arrays over all B utterances.  Output buffers are the caller's (sizes as above; the sums
+ * are known on the host before the call).  Uses 4 bytes of workspace per output row / id.
+ * Errors: SSD_EINVAL, SSD_ESHAPE (a speech row is not a multiple of 16 bytes), SSD_EWORKSPACE. */
+int ssd_select_unconfident(ssd_ctx *ctx, int B, int n_sel, const int32_t *sel /*host*/, const int32_t *cu_frames /*host*/,
+                           const int32_t *draft_len /*host [B]*/, const int32_t *draft_ctc /*dev*/,
+                           const int32_t *ctc_to_llm /*dev [V_ctc] or NULL*/, int V_ctc,
+                           const void *speech_all /*dev*/, const int32_t *cu_speech_all /*host*/,
+                           const int32_t *prompt_all /*dev*/, const int32_t *cu_prompt_all /*host*/, int d_model, int dtype,
+                           void *speech_out /*dev*/, int32_t *prompt_out /*dev*/, int32_t *draft_ids_out /*dev*/,
+                           int32_t *cu_speech_out /*host*/, int32_t *cu_prompt_out /*host*/, int32_t *cu_draft_out /*host*/);
+
+/* out[i] = src[idx[i]] for i < n on the device (src, out: dev int32; idx: host, non-negative, in range of src:
+ * the host cannot check the upper end).  The glue for picking token ids out of device arrays without a round
+ * trip, e.g. first_tok of ar_fallback = greedy_tok at each utterance's first rejected position.  Uses 4 n bytes
+ * of workspace. */
+int ssd_gather_i32(ssd_ctx *ctx, const int32_t *src /*dev*/, const int32_t *idx /*host [n]*/, int n, int32_t *out /*dev [n]*/);
+
 /* Sec. 2.2 (Eq. 4; parallel scoring through the causal mask).  For each of the Bv utterances that
  * did not pass the gate, runs the decoder over the rows [speech_emb rows; embed[prompt ids];
  * embed[draft ids]] at positions 0..n-1 and writes, for draft token i = 1..U, the final-RMSNormed
@@ -204,7 +242,9 @@ int ctc_head_gate(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*ho
  * token i) to h_verify row cu_draft[b] + i - 1.  An utterance needs S + P >= 1; U = 0 is legal.
  * speech_emb: dev [cu_speech[Bv], d_model]; prompt_ids / draft_ids: dev int32 LLM token ids
  * (ids outside [0, vocab) are clamped on the device); h_verify: dev [cu_draft[Bv], d_model], IEEE half
- * for SSD_BF16 models and fp32 for SSD_F32: an activation buffer that accept_prefix consumes. */
+ * for SSD_BF16 models and fp32 for SSD_F32: an activation buffer that accept_prefix consumes.
+ * SSD_ESHAPE if an activation matrix of the call (rows x max(d_ff, q+k+v width, d_model) elements) would
+ * reach 4 GiB: split the batch. */
 int verify_forward(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_speech /*host*/,
                    const int32_t *prompt_ids, const int32_t *cu_prompt /*host*/,
                    const int32_t *draft_ids, const int32_t *cu_draft /*host*/, int Bv,
@@ -234,7 +274,8 @@ int ssd_set_kv_cache(ssd_ctx *ctx, void *dev_ptr, size_t bytes, int64_t slots);
  * Step t = 0..n_steps-1 feeds token u_t (u_0 = first_tok) at position ctx_len + t, appends its keys and
  * values to the cache and writes u_{t+1} = lowest-index argmax of the next-token distribution to
  * out_tokens[t * Br + b] (dev, [n_steps, Br]).  Stopping at an end-of-sequence token is the caller's
- * business (truncate the row).  Needs ssd_ar_workspace_bytes(ctx, Br, n_steps) bytes of workspace. */
+ * business (truncate the row).  Needs ssd_ar_workspace_bytes(ctx, Br, n_steps) bytes of workspace.
+ * head_dim must be a multiple of 8 (SSD_ESHAPE otherwise). */
 size_t ssd_ar_workspace_bytes(const ssd_ctx *ctx, int max_utts, int max_steps);
 int ar_fallback(ssd_ctx *ctx, int Br, const int32_t *kv_start /*host [Br]*/, const int32_t *ctx_len /*host [Br]*/,
                 const int32_t *first_tok /*dev [Br]*/, int n_steps, int32_t *out_tokens /*dev [n_steps, Br]*/);

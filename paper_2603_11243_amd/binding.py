@@ -21,7 +21,7 @@ EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspac
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ssd_measure_hbm_read", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
            "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags",
-           "ctc_gate_noalloc"]
+           "ctc_gate_noalloc", "ssd_inexact_weights", "ssd_select_unconfident", "ssd_gather_i32"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
@@ -102,6 +102,12 @@ def load_library() -> C.CDLL:
     lib.ctc_head_gate.restype = i32
     lib.ctc_gate_noalloc.argtypes = [vp, vp, i32, vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, C.c_char_p, C.c_size_t]
     lib.ctc_gate_noalloc.restype = i32
+    lib.ssd_select_unconfident.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ssd_select_unconfident.restype = i32
+    lib.ssd_gather_i32.argtypes = [vp, vp, vp, i32, vp]
+    lib.ssd_gather_i32.restype = i32
+    lib.ssd_inexact_weights.argtypes = [vp]
+    lib.ssd_inexact_weights.restype = i64
     return lib
 
 
@@ -201,8 +207,13 @@ class Context:
         self._ws = buf
         self._check(self._lib.ssd_set_workspace(self._h, _ptr(buf), 0 if buf is None else buf.numel()))
 
+    def inexact_weights(self) -> int:
+        """Weight values whose conversion to the matrix-core operand type was not exact (0 for ordinary tensors)."""
+        return int(self._lib.ssd_inexact_weights(self._h))
+
     def device_flags(self) -> int:
-        """Sticky flags raised by kernels since the last call (waits for the stream); 1 = a token id was clamped."""
+        """Sticky flags raised by kernels since the last call (waits for the stream); 1 = a token id was clamped,
+        2 = an activation left the half range and was stored saturated (or a log-likelihood was not finite)."""
         f = C.c_int32(0)
         self._check(self._lib.ssd_device_flags(self._h, C.byref(f)))
         return int(f.value)
@@ -278,6 +289,42 @@ class Context:
                                             _ptr(out.get("frame_entropy")), _ptr(out.get("frame_argmax")),
                                             _ptr(out["max_entropy"]), _ptr(out["gate_pass"]),
                                             _ptr(out["draft_ctc"]), _ptr(out["draft_len"])))
+        return out
+
+    def select_unconfident(self, sel, cu_frames, draft_len_host, draft_ctc: torch.Tensor, ctc_to_llm: Optional[torch.Tensor],
+                           speech_all: Optional[torch.Tensor], cu_speech_all, prompt_all: torch.Tensor, cu_prompt_all,
+                           out: Optional[dict] = None, d_model: Optional[int] = None, dtype=None) -> dict:
+        """ssd_select_unconfident: packed verification inputs of the utterances `sel` (host indices).  `out` may
+        hold preallocated, large-enough `speech`, `prompt`, `draft_ids` tensors (their leading parts are written).
+        speech_all may be None when cu_speech_all is all zero (no speech rows are moved); then d_model and dtype
+        have to be given."""
+        sel, cuf, dl = _host_i32(sel), _host_i32(cu_frames), _host_i32(draft_len_host)
+        cs, cp = _host_i32(cu_speech_all), _host_i32(cu_prompt_all)
+        n, B = len(sel), len(cuf) - 1
+        d = int(speech_all.shape[1]) if speech_all is not None else int(d_model)
+        sdt = speech_all.dtype if speech_all is not None else dtype
+        nS = int((cs[sel + 1] - cs[sel]).sum()); nP = int((cp[sel + 1] - cp[sel]).sum()); nU = int(dl[sel].sum())
+        if out is None:
+            out = {"speech": torch.empty((nS, d), dtype=sdt, device=self.device),
+                   "prompt": torch.empty(nP, dtype=torch.int32, device=self.device),
+                   "draft_ids": torch.empty(nU, dtype=torch.int32, device=self.device)}
+        assert out["speech"].shape[0] >= nS and out["prompt"].numel() >= nP and out["draft_ids"].numel() >= nU
+        cso, cpo, cdo = (np.empty(n + 1, dtype=np.int32) for _ in range(3))
+        V = 0 if ctc_to_llm is None else int(ctc_to_llm.numel())
+        self._check(self._lib.ssd_select_unconfident(
+            self._h, B, n, sel.ctypes.data, cuf.ctypes.data, dl.ctypes.data, _ptr(draft_ctc), _ptr(ctc_to_llm), V,
+            _ptr(speech_all), cs.ctypes.data, _ptr(prompt_all), cp.ctypes.data, d, _DTYPE_CODE[sdt],
+            _ptr(out["speech"]) if nS else None, _ptr(out["prompt"]) if nP else None, _ptr(out["draft_ids"]) if nU else None,
+            cso.ctypes.data, cpo.ctypes.data, cdo.ctypes.data))
+        return {"speech": out["speech"][:nS], "prompt": out["prompt"][:nP], "draft_ids": out["draft_ids"][:nU],
+                "cu_speech": cso, "cu_prompt": cpo, "cu_draft": cdo}
+
+    def gather_i32(self, src: torch.Tensor, idx, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """out[i] = src[idx[i]] on the device (ssd_gather_i32); idx is a host array."""
+        ix = _host_i32(idx)
+        if out is None:
+            out = torch.empty(len(ix), dtype=torch.int32, device=self.device)
+        self._check(self._lib.ssd_gather_i32(self._h, _ptr(src), ix.ctypes.data, len(ix), _ptr(out)))
         return out
 
     def verify_forward(self, speech_emb: torch.Tensor, cu_speech, prompt_ids: torch.Tensor, cu_prompt,

@@ -100,6 +100,7 @@ struct ssd_ctx {
     int head_V = 0, head_V_pad = 0, head_d = 0;
     void* kv = nullptr;                      // caller-owned K/V cache: [layer][K|V][slots][d_kv] in the activation type
     int64_t kv_slots = 0;
+    int64_t inexact_weights = 0;             // weight values the half conversion could not hold exactly
     std::string err;
     Stager stager;
     Profiler prof;
@@ -329,6 +330,10 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
             scale[g] = ldexpf(1.0f, std::max(-60, std::min(60, 14 - ex)));   // largest value lands below 2^14
         }
     }
+    // values that the conversion to half cannot hold exactly are counted (ssd_inexact_weights)
+    unsigned long long* d_inexact = nullptr;
+    if ((e = dev_alloc((void**)&d_inexact, 256)) != hipSuccess) return bail(e, "hipMalloc(inexact)");
+    if ((e = hipMemsetAsync(d_inexact, 0, 256, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(inexact)");
     for (int l = 0; l < L; ++l) {
         c->norm_attn.push_back(w->norm_attn[l]); c->norm_mlp.push_back(w->norm_mlp[l]);
         void *pq = nullptr, *pg = nullptr;
@@ -336,14 +341,14 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
         c->wqkv.push_back(pq);
         if ((e = dev_alloc(&pg, (size_t)2 * dff * d * es)) != hipSuccess) return bail(e, "hipMalloc(wgu)");
         c->wgu.push_back(pg);
-        launch_pack_qkv(cfg->dtype, w->wq[l], w->wk[l], w->wv[l], pq, dq, dkv, d, cfg->head_dim, scale[4 * l + 0], c->stream);
-        launch_pack_gate_up(cfg->dtype, w->w_gate[l], w->w_up[l], pg, dff, d, scale[4 * l + 2], c->stream);
+        launch_pack_qkv(cfg->dtype, w->wq[l], w->wk[l], w->wv[l], pq, dq, dkv, d, cfg->head_dim, scale[4 * l + 0], d_inexact, c->stream);
+        launch_pack_gate_up(cfg->dtype, w->w_gate[l], w->w_up[l], pg, dff, d, scale[4 * l + 2], d_inexact, c->stream);
         if (half) {
             void *po = nullptr, *pd = nullptr;
             if ((e = dev_alloc(&po, (size_t)d * dq * 2)) != hipSuccess) return bail(e, "hipMalloc(wo)");
             if ((e = dev_alloc(&pd, (size_t)d * dff * 2)) != hipSuccess) return bail(e, "hipMalloc(w_down)");
-            launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, scale[4 * l + 1], c->stream);
-            launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, scale[4 * l + 3], c->stream);
+            launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, scale[4 * l + 1], d_inexact, c->stream);
+            launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, scale[4 * l + 3], d_inexact, c->stream);
             c->wo.push_back(po); c->w_down.push_back(pd);
             struct { const void* src; int N, K; std::vector<void*>* dst; } copies[4] = {
                 {pq, dq + 2 * dkv, d, &c->s_qkv}, {po, d, dq, &c->s_o}, {pg, 2 * dff, d, &c->s_gu}, {pd, d, dff, &c->s_down}};
@@ -364,7 +369,7 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
     if (half) {
         void* pl = nullptr;
         if ((e = dev_alloc(&pl, (size_t)cfg->vocab * d * 2)) != hipSuccess) return bail(e, "hipMalloc(lm_head)");
-        launch_convert_weight(cfg->dtype, w->lm_head, pl, cfg->vocab, d, scale[4 * L], c->stream);
+        launch_convert_weight(cfg->dtype, w->lm_head, pl, cfg->vocab, d, scale[4 * L], d_inexact, c->stream);
         c->lm_head = pl;
         c->ds_lm = 1.0f / scale[4 * L];
     }
@@ -382,11 +387,16 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
         return bail(e, "hipMemcpyAsync(rope)");
     if ((e = dev_alloc((void**)&c->dev_flags, 256)) != hipSuccess) return bail(e, "hipMalloc(flags)");
     if ((e = hipMemsetAsync(c->dev_flags, 0, 256, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync(flags)");
+    unsigned long long n_inexact = 0;
+    if ((e = hipMemcpyAsync(&n_inexact, d_inexact, 8, hipMemcpyDeviceToHost, c->stream)) != hipSuccess) return bail(e, "hipMemcpyAsync(inexact)");
     if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(e, "weight packing");
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "weight packing launch");
+    c->inexact_weights = (int64_t)n_inexact;
     *out = c;
     return SSD_OK;
 }
+
+int64_t ssd_inexact_weights(const ssd_ctx* ctx) { return ctx ? ctx->inexact_weights : -1; }
 
 void ssd_destroy(ssd_ctx* c) {
     if (!c) return;
@@ -519,6 +529,77 @@ int ssd_plan_batches(const int32_t* lengths, int n, int64_t max_tokens, int padd
     }
     batch_start[++nb] = n;
     *n_batches = nb;
+    return SSD_OK;
+}
+
+int ssd_select_unconfident(ssd_ctx* ctx, int B, int n_sel, const int32_t* sel, const int32_t* cu_frames,
+                           const int32_t* draft_len, const int32_t* draft_ctc, const int32_t* ctc_to_llm, int V_ctc,
+                           const void* speech_all, const int32_t* cu_speech_all, const int32_t* prompt_all,
+                           const int32_t* cu_prompt_all, int d_model, int dtype, void* speech_out, int32_t* prompt_out,
+                           int32_t* draft_ids_out, int32_t* cu_speech_out, int32_t* cu_prompt_out, int32_t* cu_draft_out) {
+    if (!ctx) return SSD_EINVAL;
+    if (!sel || !cu_frames || !draft_len || !cu_speech_all || !cu_prompt_all || !cu_speech_out || !cu_prompt_out || !cu_draft_out)
+        return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: NULL host array");
+    if (B <= 0 || n_sel <= 0 || n_sel > B) return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: need 0 < n_sel <= B");
+    if (d_model <= 0 || (dtype != SSD_F32 && dtype != SSD_BF16)) return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: bad d_model or dtype");
+    if (ctc_to_llm && V_ctc <= 0) return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: V_ctc must be positive with a table");
+    if (!check_cu(cu_frames, B, true) || !check_cu(cu_speech_all, B, false) || !check_cu(cu_prompt_all, B, false))
+        return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: malformed cu_* array");
+    const size_t row_bytes = (size_t)d_model * elem_size(dtype);
+    if (row_bytes % 16) return fail(ctx, SSD_ESHAPE, "ssd_select_unconfident: a speech row must be a multiple of 16 bytes");
+    int64_t nS = 0, nP = 0, nU = 0;
+    cu_speech_out[0] = cu_prompt_out[0] = cu_draft_out[0] = 0;
+    for (int k = 0; k < n_sel; ++k) {
+        const int b = sel[k];
+        if (b < 0 || b >= B) return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: sel[%d] = %d outside [0, %d)", k, b, B);
+        if (draft_len[b] < 0 || draft_len[b] > cu_frames[b + 1] - cu_frames[b])
+            return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: draft_len[%d] = %d does not fit the utterance's %d frames", b,
+                        draft_len[b], cu_frames[b + 1] - cu_frames[b]);
+        nS += cu_speech_all[b + 1] - cu_speech_all[b];
+        nP += cu_prompt_all[b + 1] - cu_prompt_all[b];
+        nU += draft_len[b];
+        if (nS + nP + nU > 0x3fffffff) return fail(ctx, SSD_ESHAPE, "ssd_select_unconfident: too many rows");
+        cu_speech_out[k + 1] = (int32_t)nS; cu_prompt_out[k + 1] = (int32_t)nP; cu_draft_out[k + 1] = (int32_t)nU;
+    }
+    if ((nS && (!speech_all || !speech_out)) || (nP && (!prompt_all || !prompt_out)) || (nU && (!draft_ctc || !draft_ids_out)))
+        return fail(ctx, SSD_EINVAL, "ssd_select_unconfident: NULL data pointer");
+    const size_t oS = 0, oP = align_up((size_t)nS * 4), oU = oP + align_up((size_t)nP * 4), need = oU + align_up((size_t)nU * 4);
+    if (!ctx->ws || ctx->ws_bytes < need) return fail(ctx, SSD_EWORKSPACE, "ssd_select_unconfident: workspace of %zu bytes needed, %zu set", need, ctx->ws_bytes);
+    // source index of every packed output row / id
+    std::vector<char> meta(need);
+    int32_t* iS = reinterpret_cast<int32_t*>(meta.data() + oS);
+    int32_t* iP = reinterpret_cast<int32_t*>(meta.data() + oP);
+    int32_t* iU = reinterpret_cast<int32_t*>(meta.data() + oU);
+    for (int k = 0; k < n_sel; ++k) {
+        const int b = sel[k];
+        for (int i = cu_speech_all[b]; i < cu_speech_all[b + 1]; ++i) *iS++ = i;
+        for (int i = cu_prompt_all[b]; i < cu_prompt_all[b + 1]; ++i) *iP++ = i;
+        for (int i = 0; i < draft_len[b]; ++i) *iU++ = cu_frames[b] + i;       // ctc_gate writes utterance b's draft at cu_frames[b]
+    }
+    char* ws = static_cast<char*>(ctx->ws);
+    int rc = upload(ctx, meta.data(), ws, need);
+    if (rc != SSD_OK) return rc;
+    {
+        ProfScope ps(ctx, SSD_PROF_OTHER);
+        launch_gather_rows(speech_all, reinterpret_cast<const int32_t*>(ws + oS), (int)nS, (int64_t)row_bytes, speech_out, ctx->stream);
+        launch_gather_ids(prompt_all, reinterpret_cast<const int32_t*>(ws + oP), (int)nP, nullptr, 0, prompt_out, ctx->stream);
+        launch_gather_ids(draft_ctc, reinterpret_cast<const int32_t*>(ws + oU), (int)nU, ctc_to_llm, V_ctc, draft_ids_out, ctx->stream);
+    }
+    HIP_TRY(ctx, hipGetLastError());
+    return SSD_OK;
+}
+
+int ssd_gather_i32(ssd_ctx* ctx, const int32_t* src, const int32_t* idx, int n, int32_t* out) {
+    if (!ctx) return SSD_EINVAL;
+    if (n < 0 || (n && (!src || !idx || !out))) return fail(ctx, SSD_EINVAL, "ssd_gather_i32: bad argument");
+    for (int i = 0; i < n; ++i)
+        if (idx[i] < 0) return fail(ctx, SSD_EINVAL, "ssd_gather_i32: idx[%d] is negative", i);
+    const size_t need = align_up((size_t)n * 4);
+    if (n && (!ctx->ws || ctx->ws_bytes < need)) return fail(ctx, SSD_EWORKSPACE, "ssd_gather_i32: workspace of %zu bytes needed", need);
+    int rc = upload(ctx, idx, ctx->ws, (size_t)n * 4);
+    if (rc != SSD_OK) return rc;
+    launch_gather_ids(src, static_cast<const int32_t*>(ctx->ws), n, nullptr, 0, out, ctx->stream);
+    HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }
 
@@ -697,6 +778,12 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     if ((sum_S && !speech_emb) || (sum_P && !prompt_ids) || (Mv && (!draft_ids || !h_verify)))
         return fail(ctx, SSD_EINVAL, "verify_forward: NULL data pointer");
     if (M > 0x3fffffff) return fail(ctx, SSD_ESHAPE, "verify_forward: too many rows");
+    {   // the GEMM loaders address an operand matrix with 32-bit byte offsets: each must stay below 4 GiB
+        const int64_t widest = std::max<int64_t>({(int64_t)m.d_ff, (int64_t)(m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, (int64_t)m.d_model});
+        if (M * widest * (int64_t)elem_size(m.dtype) >= ((int64_t)1 << 32))
+            return fail(ctx, SSD_ESHAPE, "verify_forward: %lld rows of %lld columns exceed the 4 GiB an activation matrix may have; "
+                        "split the batch (ssd_plan_batches)", (long long)M, (long long)widest);
+    }
     const int tile_rows = attn_tile_rows(m.dtype);
     for (int b = 0; b < Bv; ++b) {
         const int S = cu_speech[b + 1] - cu_speech[b], P = cu_prompt[b + 1] - cu_prompt[b], U = cu_draft[b + 1] - cu_draft[b];
@@ -767,11 +854,11 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     const int Mvi = (int)Mv;
     bool compact = false;
     for (int l = 0; l < m.n_layers; ++l) {
-        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, st); }
+        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st); }
         pending = 1;
         if (m.dtype == SSD_BF16) {
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
-                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, rope_rows, st); }
+                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, rope_rows, ctx->dev_flags, st); }
             { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
             float* xr = x; const void* attr = att; int rows = Mi;
             if (l == m.n_layers - 1) {
@@ -782,9 +869,9 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
             }
             const int64_t stride = (int64_t)rows * d;
             { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], ctx->s_o[l], xr, partials, rows, d, dq, ctx->ds_o[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, st); }
+            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, ctx->dev_flags, st); }
             pending = 1;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, st); }
             { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
@@ -793,7 +880,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
             if (kv_start) launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
             launch_attn_f32((const float*)qkv, (float*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, m.head_dim, st);
             launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Mi, d, dq, F32_ADD, st);
-            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, st);
             launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Mi, 2 * m.d_ff, d, F32_STORE, st);
             launch_swiglu_f32(gu, (float*)h, Mi, m.d_ff, st);
             launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Mi, d, m.d_ff, F32_ADD, st);
@@ -802,10 +889,10 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     // final RMSNorm of the positions that score a draft token
     if (compact) {
         ProfScope ps(ctx, SSD_PROF_OTHER);
-        launch_rmsnorm(m.dtype, x_c, ctx->norm_final, nullptr, Mvi, d, m.rms_eps, h_verify, partials, pending, (int64_t)Mvi * d, st);
+        launch_rmsnorm(m.dtype, x_c, ctx->norm_final, nullptr, Mvi, d, m.rms_eps, h_verify, partials, pending, (int64_t)Mvi * d, ctx->dev_flags, st);
     } else {
         ProfScope ps(ctx, SSD_PROF_OTHER);
-        launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, Mvi, d, m.rms_eps, h_verify, partials, pending, split_stride, st);
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, Mvi, d, m.rms_eps, h_verify, partials, pending, split_stride, ctx->dev_flags, st);
     }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
@@ -894,6 +981,7 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
     if (Br <= 0 || n_steps <= 0) return fail(ctx, SSD_EINVAL, "ar_fallback: Br and n_steps must be positive");
     if (!ctx->kv) return fail(ctx, SSD_EINVAL, "ar_fallback: no K/V cache set");
     const ssd_model_cfg& m = ctx->cfg;
+    if (m.head_dim % 8) return fail(ctx, SSD_ESHAPE, "ar_fallback: head_dim must be a multiple of 8 (got %d)", m.head_dim);
     for (int b = 0; b < Br; ++b) {
         if (ctx_len[b] < 1) return fail(ctx, SSD_EINVAL, "ar_fallback: utterance %d has an empty context", b);
         if (ctx_len[b] + n_steps > m.max_positions)
@@ -941,7 +1029,7 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
         launch_embed_rows(m.dtype, nullptr, ctx->embed, nullptr, tok_in, d_row_src, Br, d, m.vocab, x, ctx->dev_flags, st);
         int pending = 1;
         for (int l = 0; l < m.n_layers; ++l) {
-            launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st);
             pending = 1;
             if (m.dtype == SSD_BF16) {
                 // few rows, head_dim 128: the QKV projection stays K-split and the decode attention finishes it
@@ -949,16 +1037,16 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
                     ? launch_gemm_qkv_partial((const uint16_t*)a, ctx->s_qkv[l], qkv_part, Br, d, dq + 2 * dkv, ctx->ds_qkv[l], st) : 0;
                 if (qsplits) {
                     launch_decode_attn_fused(qkv_part, qsplits, ctx->rope_tab, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br,
-                                             m.n_q_heads, m.n_kv_heads, att, st);
+                                             m.n_q_heads, m.n_kv_heads, att, ctx->dev_flags, st);
                 } else {
                     launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
-                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), nullptr, st);
+                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), nullptr, ctx->dev_flags, st);
                     launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
                 }
                 pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
-                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st);
                 pending = 1;
-                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], st);
+                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, st);
                 pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], st);
             } else {
                 float* gu = reinterpret_cast<float*>(ws + p.gu);
@@ -967,20 +1055,20 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
                 launch_kv_store(m.dtype, qkv, d_slot, Br, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
                 launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
                 launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Br, d, dq, F32_ADD, st);
-                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, nullptr, 1, 0, st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, st);
                 launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Br, 2 * m.d_ff, d, F32_STORE, st);
                 launch_swiglu_f32(gu, (float*)h, Br, m.d_ff, st);
                 launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Br, d, m.d_ff, F32_ADD, st);
             }
         }
-        launch_rmsnorm(m.dtype, x, ctx->norm_final, nullptr, Br, d, m.rms_eps, hfin, partials, pending, split_stride, st);
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, nullptr, Br, d, m.rms_eps, hfin, partials, pending, split_stride, ctx->dev_flags, st);
         int32_t* tok_out = out_tokens + (size_t)t * Br;
         if (m.dtype == SSD_BF16) {
             float2* part_ms = reinterpret_cast<float2*>(ws + p.part_ms);
             float* tgt = reinterpret_cast<float*>(ws + p.tgt);
             int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
             launch_lmhead_mfma((const uint16_t*)hfin, (const uint16_t*)ctx->lm_head, tok_in, Br, d, m.vocab, part_ms, tgt, part_arg, true, ctx->ds_lm, st);
-            launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), Br, logp, tok_out, st);
+            launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), Br, logp, tok_out, ctx->dev_flags, st);
         } else {
             launch_lmhead_f32((const float*)hfin, (const float*)ctx->lm_head, tok_in, Br, d, m.vocab, logp, tok_out, st);
         }
@@ -1000,6 +1088,8 @@ int accept_prefix(ssd_ctx* ctx, const void* h_verify, const int32_t* draft_ids, 
     const int64_t Mv = cu_draft[Bv];
     if (Mv && (!h_verify || !draft_ids || !draft_logp)) return fail(ctx, SSD_EINVAL, "accept_prefix: NULL data pointer");
     const ssd_model_cfg& m = ctx->cfg;
+    if (Mv * (int64_t)m.d_model * (int64_t)elem_size(m.dtype) >= ((int64_t)1 << 32))
+        return fail(ctx, SSD_ESHAPE, "accept_prefix: %lld rows exceed the 4 GiB the hidden rows may have; split the batch", (long long)Mv);
     const AcceptPlan p = plan_accept(m, Mv, Bv);
     if (!ctx->ws || ctx->ws_bytes < p.total)
         return fail(ctx, SSD_EWORKSPACE, "accept_prefix: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
@@ -1015,7 +1105,7 @@ int accept_prefix(ssd_ctx* ctx, const void* h_verify, const int32_t* draft_ids, 
         int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
         launch_lmhead_mfma((const uint16_t*)h_verify, (const uint16_t*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,
                            part_ms, tgt, part_arg, greedy_tok != nullptr, ctx->ds_lm, st);
-        launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), (int)Mv, draft_logp, greedy_tok, st);
+        launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), (int)Mv, draft_logp, greedy_tok, ctx->dev_flags, st);
     } else {
         launch_lmhead_f32((const float*)h_verify, (const float*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,
                           draft_logp, greedy_tok, st);

@@ -147,6 +147,7 @@ struct DecodeFused {
     const float* part; int n_splits; int64_t split_stride;    // split_stride = rows * (d_q + 2 d_kv)
     const float2* rope_tab;                                   // [position][64] (cos, sin)
     f16_t* kc_w; f16_t* vc_w;                                 // writable views of the cache
+    int32_t* flags;                                           // sticky device flags (SSD_FLAG_ACT_OVERFLOW on a saturated store)
     // The new row's position is the number of rows its utterance has in the cache (cache row i of an
     // utterance is position i), and its slot is kv_start + that number: no further index arrays.
 };
@@ -231,6 +232,7 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         const int64_t row_off = (int64_t)b * (d_q + 2 * d_kv);
         const int p = n;                                     // position of the new token
         float s_new = 0.f;
+        bool bad = false;
         uint4 vw = make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[e] = 0.f;
@@ -239,15 +241,15 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
             rope_entries(fu, dc, p, cs);
             rotated_chunk(fu, row_off, h * HD, dc, cs, qf);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) qf[e] = (float)(_Float16)qf[e] * sc;      // q is rounded like a stored row
+            for (int e = 0; e < 8; ++e) qf[e] = f16_to_f32(f32_to_f16_sat(qf[e], bad)) * sc;      // q is rounded (and saturated) like a stored row
             if (wave == 0) {
                 float kn[8], vn[8];
                 rotated_chunk(fu, row_off, d_q + kvh * HD, dc, cs, kn);
                 sum_splits8(fu, row_off, d_q + d_kv + kvh * HD + dc * 8, vn);
                 // the cache holds half precision: the new row takes part in this step with the values later steps read
                 uint4 kw;
-                kw.x = pack_f16x2(kn[0], kn[1]); kw.y = pack_f16x2(kn[2], kn[3]); kw.z = pack_f16x2(kn[4], kn[5]); kw.w = pack_f16x2(kn[6], kn[7]);
-                vw.x = pack_f16x2(vn[0], vn[1]); vw.y = pack_f16x2(vn[2], vn[3]); vw.z = pack_f16x2(vn[4], vn[5]); vw.w = pack_f16x2(vn[6], vn[7]);
+                kw.x = pack_f16x2_sat(kn[0], kn[1], bad); kw.y = pack_f16x2_sat(kn[2], kn[3], bad); kw.z = pack_f16x2_sat(kn[4], kn[5], bad); kw.w = pack_f16x2_sat(kn[6], kn[7], bad);
+                vw.x = pack_f16x2_sat(vn[0], vn[1], bad); vw.y = pack_f16x2_sat(vn[2], vn[3], bad); vw.z = pack_f16x2_sat(vn[4], vn[5], bad); vw.w = pack_f16x2_sat(vn[6], vn[7], bad);
                 if (h % (n_q_heads / n_kv_heads) == 0) {
                     const int64_t so = ((int64_t)kv_start[b] + n) * d_kv + kvh * HD + dc * 8;
                     *reinterpret_cast<uint4*>(fu.kc_w + so) = kw;
@@ -258,6 +260,7 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
                 for (int e = 0; e < 8; ++e) s_new = fmaf(qf[e], (float)kh[e], s_new);
             }
         }
+        if (bad) raise_flag(fu.flags, SSD_FLAG_ACT_OVERFLOW);
         s_new = group_allreduce<16>(s_new, OpSum());          // lanes 0..15 hold the score of the new row
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[e] = __shfl(qf[e], dc);
@@ -361,10 +364,10 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
 
 void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
                               const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
-                              void* out, hipStream_t st) {
+                              void* out, int32_t* flags, hipStream_t st) {
     if (Br <= 0) return;
     const int64_t stride = (int64_t)Br * (n_q_heads + 2 * n_kv_heads) * 128;
-    DecodeFused fu{qkv_part, n_splits, stride, reinterpret_cast<const float2*>(rope_tab), (f16_t*)kc, (f16_t*)vc};
+    DecodeFused fu{qkv_part, n_splits, stride, reinterpret_cast<const float2*>(rope_tab), (f16_t*)kc, (f16_t*)vc, flags};
     hipLaunchKernelGGL(decode_attn_hd128_kernel<true>, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, nullptr, (const f16_t*)kc,
                        (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, fu);
 }

@@ -30,6 +30,41 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
 }
 __device__ __forceinline__ float f16_to_f32(f16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
 
+// Activation stores in half precision saturate: a value beyond the largest finite half (65504) is stored as
+// +-65504 instead of +-inf, and `bad` remembers that it happened (also for NaN) so that the kernel can raise
+// the sticky SSD_FLAG_ACT_OVERFLOW once at its end.  One compare and one v_med3_f32 per stored value.
+constexpr float F16_MAX = 65504.0f;
+__device__ __forceinline__ f16_t f32_to_f16_sat(float v, bool& bad) {
+    bad |= !(fabsf(v) <= F16_MAX);
+    return f32_to_f16(__builtin_amdgcn_fmed3f(v, -F16_MAX, F16_MAX));
+}
+__device__ __forceinline__ uint32_t pack_f16x2_sat(float lo, float hi, bool& bad) {
+    return (uint32_t)f32_to_f16_sat(lo, bad) | ((uint32_t)f32_to_f16_sat(hi, bad) << 16);
+}
+// The same for kernels that store many values per lane: the common pass only tracks the largest magnitude
+// (one v_max_f32 per value) and converts plainly; a lane that saw a value beyond the half range repeats
+// its stores with f16_store<true>, which clamps.  (A NaN passes through both; it shows up as a non-finite
+// likelihood, which raises the same flag.)
+__device__ __forceinline__ float track_peak(float peak, float v) {
+    float r;
+    asm("v_max_f32 %0, %1, |%2|" : "=v"(r) : "v"(peak), "v"(v));
+    return r;
+}
+template <bool CLAMP>
+__device__ __forceinline__ f16_t f16_store(float v, float& peak) {
+    if constexpr (CLAMP) return f32_to_f16(__builtin_amdgcn_fmed3f(v, -F16_MAX, F16_MAX));
+    peak = track_peak(peak, v);
+    return f32_to_f16(v);
+}
+template <bool CLAMP>
+__device__ __forceinline__ uint32_t f16x2_store(float lo, float hi, float& peak) {
+    return (uint32_t)f16_store<CLAMP>(lo, peak) | ((uint32_t)f16_store<CLAMP>(hi, peak) << 16);
+}
+// flag bits are those of enum ssd_device_flag (a vector atomic: several kernels may raise different bits)
+__device__ __forceinline__ void raise_flag(int32_t* flags, int bit) {
+    if (flags) atomicOr(flags, bit);
+}
+
 // Data-parallel-primitive lane moves inside a row of 16 lanes.
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {

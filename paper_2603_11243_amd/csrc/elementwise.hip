@@ -1,6 +1,7 @@
 // Memory-bound helpers of the decoder forward: input-row assembly, RMSNorm, weight re-layout,
 // and the first-failing-token scan of the acceptance rule.
 #include <algorithm>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "ssd_internal.h"
@@ -22,7 +23,7 @@ __global__ void __launch_bounds__(256) embed_rows_kernel(const T* __restrict__ s
     if (code & (SRC_DRAFT | SRC_PROMPT)) {
         const int raw = (code & SRC_DRAFT) ? draft_ids[code & SRC_MASK] : prompt_ids[code & SRC_MASK];
         const int id = raw < 0 ? 0 : (raw >= vocab ? vocab - 1 : raw);
-        if (id != raw && flags && threadIdx.x == 0) *flags = SSD_FLAG_TOKEN_CLAMPED;   // sticky until read
+        if (id != raw && threadIdx.x == 0) raise_flag(flags, SSD_FLAG_TOKEN_CLAMPED);   // sticky until read
         src = embed + (int64_t)id * d;
     } else {
         src = speech_emb + (int64_t)code * d;
@@ -60,6 +61,22 @@ void launch_gather_rows(const void* src, const int32_t* row_idx, int n_rows, int
                        (int)(row_bytes / 16), static_cast<uint4*>(dst));
 }
 
+// out[i] = table ? table[clamp(src[idx[i]], 0, n_table - 1)] : src[idx[i]]   (token-id gathers between the gate and
+// the verification pass: prompt ids of the selected utterances, CTC draft symbols mapped to LLM token ids)
+__global__ void __launch_bounds__(256) gather_ids_kernel(const int32_t* __restrict__ src, const int32_t* __restrict__ idx, int n,
+                                                         const int32_t* __restrict__ table, int n_table, int32_t* __restrict__ out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    int v = src[idx[i]];
+    if (table) v = table[min(max(v, 0), n_table - 1)];
+    out[i] = v;
+}
+
+void launch_gather_ids(const int32_t* src, const int32_t* idx, int n, const int32_t* table, int n_table, int32_t* out, hipStream_t st) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(gather_ids_kernel, dim3((n + 255) / 256), dim3(256), 0, st, src, idx, n, table, n_table, out);
+}
+
 // ---------------------------------------------------------------------------------------------
 // RMSNorm: out[r] = x[row] * gain / sqrt(mean(x[row]^2) + eps), row = row_idx ? row_idx[r] : r.
 // One wavefront per row; statistics in fp32.  d must be a multiple of 4.
@@ -68,7 +85,7 @@ template <typename T, int NV>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                       const int32_t* __restrict__ row_idx, int n_rows, int d,
                                                       float eps, T* __restrict__ out, const float* __restrict__ partials,
-                                                      int n_splits, int64_t split_stride) {
+                                                      int n_splits, int64_t split_stride, int32_t* __restrict__ flags) {
     // the row stays in registers between the statistic and the scaling: NV float4 per lane (d <= 256*NV)
     const int lane = threadIdx.x % 64;
     const int r = blockIdx.x * 4 + threadIdx.x / 64;
@@ -118,21 +135,30 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
     ss = group_allreduce<64>(ss, OpSum());
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     T* dst = out + (int64_t)r * d;
+    float peak = 0.f;
+    auto store_row = [&](auto clamp_c) {
+        constexpr bool CLAMP = decltype(clamp_c)::value;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-        const int i = lane + 64 * j;
-        if (i >= n4) continue;
-        if constexpr (sizeof(T) == 2) {
-            const uint2 g = g16[j];
-            uint2 o;
-            o.x = pack_f16x2(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x));
-            o.y = pack_f16x2(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y));
-            reinterpret_cast<uint2*>(dst)[i] = o;
-        } else {
-            const float4 g = reinterpret_cast<const float4*>(gain)[i];
-            reinterpret_cast<float4*>(dst)[i] =
-                make_float4(v[j].x * inv * g.x, v[j].y * inv * g.y, v[j].z * inv * g.z, v[j].w * inv * g.w);
+        for (int j = 0; j < NV; ++j) {
+            const int i = lane + 64 * j;
+            if (i >= n4) continue;
+            if constexpr (sizeof(T) == 2) {
+                const uint2 g = g16[j];
+                uint2 o;
+                o.x = f16x2_store<CLAMP>(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x), peak);
+                o.y = f16x2_store<CLAMP>(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y), peak);
+                reinterpret_cast<uint2*>(dst)[i] = o;
+            } else {
+                const float4 g = reinterpret_cast<const float4*>(gain)[i];
+                reinterpret_cast<float4*>(dst)[i] =
+                    make_float4(v[j].x * inv * g.x, v[j].y * inv * g.y, v[j].z * inv * g.z, v[j].w * inv * g.w);
+            }
         }
+    };
+    store_row(std::false_type());
+    if (!(peak <= F16_MAX)) {                               // a gain large enough to leave the half range: store saturated
+        store_row(std::true_type());
+        raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
     }
 }
 
@@ -143,7 +169,7 @@ template <typename T, int MAXV>
 __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                           const int32_t* __restrict__ row_idx, int d, float eps,
                                                           T* __restrict__ out, const float* __restrict__ partials,
-                                                          int n_splits, int64_t split_stride) {
+                                                          int n_splits, int64_t split_stride, int32_t* __restrict__ flags) {
     __shared__ float red[4];
     const int r = blockIdx.x;
     const int64_t row = row_idx ? row_idx[r] : r;
@@ -183,36 +209,45 @@ __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x,
     ss = (red[0] + red[1]) + (red[2] + red[3]);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     T* dst = out + (int64_t)r * d;
+    float peak = 0.f;
+    auto store_row = [&](auto clamp_c) {
+        constexpr bool CLAMP = decltype(clamp_c)::value;
 #pragma unroll
-    for (int k = 0; k < MAXV; ++k) {
-        const int i = threadIdx.x + k * 256;
-        if (i >= n4) continue;
-        if constexpr (sizeof(T) == 2) {
-            const uint2 g = g16[k];
-            uint2 o;
-            o.x = pack_f16x2(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x));
-            o.y = pack_f16x2(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y));
-            reinterpret_cast<uint2*>(dst)[i] = o;
-        } else {
-            const float4 g = reinterpret_cast<const float4*>(gain)[i];
-            reinterpret_cast<float4*>(dst)[i] = make_float4(v[k].x * inv * g.x, v[k].y * inv * g.y, v[k].z * inv * g.z, v[k].w * inv * g.w);
+        for (int k = 0; k < MAXV; ++k) {
+            const int i = threadIdx.x + k * 256;
+            if (i >= n4) continue;
+            if constexpr (sizeof(T) == 2) {
+                const uint2 g = g16[k];
+                uint2 o;
+                o.x = f16x2_store<CLAMP>(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x), peak);
+                o.y = f16x2_store<CLAMP>(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y), peak);
+                reinterpret_cast<uint2*>(dst)[i] = o;
+            } else {
+                const float4 g = reinterpret_cast<const float4*>(gain)[i];
+                reinterpret_cast<float4*>(dst)[i] = make_float4(v[k].x * inv * g.x, v[k].y * inv * g.y, v[k].z * inv * g.z, v[k].w * inv * g.w);
+            }
         }
+    };
+    store_row(std::false_type());
+    if (!(peak <= F16_MAX)) {
+        store_row(std::true_type());
+        raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
     }
 }
 
 void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d, float eps,
-                    void* out, const float* partials, int n_splits, int64_t split_stride, hipStream_t st) {
+                    void* out, const float* partials, int n_splits, int64_t split_stride, int32_t* flags, hipStream_t st) {
     if (n_rows <= 0) return;
     if (n_rows <= 512 && d <= 4096 && n_splits <= SKINNY_MAX_SPLITS) {
         if (dtype == SSD_BF16)
-            hipLaunchKernelGGL((rmsnorm_row_kernel<bf16_t, 4>), dim3(n_rows), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, d, eps, (bf16_t*)out, partials, n_splits, split_stride);
+            hipLaunchKernelGGL((rmsnorm_row_kernel<bf16_t, 4>), dim3(n_rows), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, d, eps, (bf16_t*)out, partials, n_splits, split_stride, flags);
         else
-            hipLaunchKernelGGL((rmsnorm_row_kernel<float, 4>), dim3(n_rows), dim3(256), 0, st, x, (const float*)gain, row_idx, d, eps, (float*)out, partials, n_splits, split_stride);
+            hipLaunchKernelGGL((rmsnorm_row_kernel<float, 4>), dim3(n_rows), dim3(256), 0, st, x, (const float*)gain, row_idx, d, eps, (float*)out, partials, n_splits, split_stride, flags);
         return;
     }
     const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
 #define SSD_RMSNORM(T, NV) \
-    hipLaunchKernelGGL((rmsnorm_kernel<T, NV>), grid, block, 0, st, x, (const T*)gain, row_idx, n_rows, d, eps, (T*)out, partials, n_splits, split_stride)
+    hipLaunchKernelGGL((rmsnorm_kernel<T, NV>), grid, block, 0, st, x, (const T*)gain, row_idx, n_rows, d, eps, (T*)out, partials, n_splits, split_stride, flags)
     if (dtype == SSD_BF16) {
         if (d <= 2048) SSD_RMSNORM(bf16_t, 8);
         else if (d <= 4096) SSD_RMSNORM(bf16_t, 16);
@@ -230,8 +265,24 @@ void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_id
 // tensor's largest magnitude, so every bf16 value (8 significant bits) is represented exactly.
 // fp32 weights are copied unchanged (scale 1).
 template <typename T> struct Packed;
-template <> struct Packed<float> { typedef float type; static __device__ __forceinline__ float cvt(float v, float) { return v; } };
-template <> struct Packed<bf16_t> { typedef f16_t type; static __device__ __forceinline__ f16_t cvt(bf16_t v, float scale) { return f32_to_f16(bf16_to_f32(v) * scale); } };
+// `lost` counts the values whose half representation differs from w * scale: a bf16 value keeps all its 8
+// significant bits only within 31 binades below the largest magnitude of its tensor (which lands just below
+// 2^14, against the smallest half subnormal 2^-24); smaller ones are rounded to the subnormal grid.
+template <> struct Packed<float> { typedef float type; static __device__ __forceinline__ float cvt(float v, float, unsigned& lost) { return v; } };
+template <> struct Packed<bf16_t> {
+    typedef f16_t type;
+    static __device__ __forceinline__ f16_t cvt(bf16_t v, float scale, unsigned& lost) {
+        const float t = bf16_to_f32(v) * scale;
+        const f16_t h = f32_to_f16(t);
+        lost += (f16_to_f32(h) != t) ? 1u : 0u;
+        return h;
+    }
+};
+// one atomic per wavefront that lost something (at context creation only)
+__device__ __forceinline__ void add_lost(unsigned lost, unsigned long long* counter) {
+    lost = (unsigned)group_allreduce_i<64>((int)lost, [] __device__(int a, int b) { return a + b; });
+    if (counter && lost && threadIdx.x % 64 == 0) atomicAdd(counter, (unsigned long long)lost);
+}
 
 template <typename T>
 __global__ void absmax_kernel(const T* __restrict__ w, int64_t n, unsigned int* __restrict__ out) {
@@ -252,15 +303,19 @@ void launch_absmax(int dtype, const void* w, int64_t n, unsigned int* out, hipSt
 }
 
 template <typename T>
-__global__ void convert_rows_kernel(const T* __restrict__ w, typename Packed<T>::type* __restrict__ out, int cols, float scale) {
+__global__ void convert_rows_kernel(const T* __restrict__ w, typename Packed<T>::type* __restrict__ out, int cols, float scale,
+                                    unsigned long long* __restrict__ inexact) {
     const T* src = w + (int64_t)blockIdx.x * cols;
     typename Packed<T>::type* dst = out + (int64_t)blockIdx.x * cols;
-    for (int i = threadIdx.x; i < cols; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+    unsigned lost = 0;
+    for (int i = threadIdx.x; i < cols; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale, lost);
+    add_lost(lost, inexact);
 }
 
-void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, hipStream_t st) {
-    if (dtype == SSD_BF16) hipLaunchKernelGGL(convert_rows_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)w, (f16_t*)out, cols, scale);
-    else hipLaunchKernelGGL(convert_rows_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)w, (float*)out, cols, scale);
+void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, unsigned long long* inexact,
+                           hipStream_t st) {
+    if (dtype == SSD_BF16) hipLaunchKernelGGL(convert_rows_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)w, (f16_t*)out, cols, scale, inexact);
+    else hipLaunchKernelGGL(convert_rows_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)w, (float*)out, cols, scale, inexact);
 }
 //
 // Fused QKV: rows [q heads | k heads | v heads].  Inside every rotary head (q and k) rows are
@@ -270,7 +325,7 @@ void launch_convert_weight(int dtype, const void* w, void* out, int rows, int co
 template <typename T>
 __global__ void pack_qkv_kernel(const T* __restrict__ wq, const T* __restrict__ wk, const T* __restrict__ wv,
                                 typename Packed<T>::type* __restrict__ out, int d_q, int d_kv, int d_model, int head_dim,
-                                int permute, float scale) {
+                                int permute, float scale, unsigned long long* __restrict__ inexact) {
     const int p = blockIdx.x;                       // packed row
     int orig = p;
     const int d_rot = d_q + d_kv;
@@ -285,18 +340,20 @@ __global__ void pack_qkv_kernel(const T* __restrict__ wq, const T* __restrict__ 
                  : orig < d_q + d_kv ? wk + (int64_t)(orig - d_q) * d_model
                  : wv + (int64_t)(orig - d_q - d_kv) * d_model;
     typename Packed<T>::type* dst = out + (int64_t)p * d_model;
-    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+    unsigned lost = 0;
+    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale, lost);
+    add_lost(lost, inexact);
 }
 
 void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, void* out, int d_q, int d_kv,
-                     int d_model, int head_dim, float scale, hipStream_t st) {
+                     int d_model, int head_dim, float scale, unsigned long long* inexact, hipStream_t st) {
     const int rows = d_q + 2 * d_kv;
     if (dtype == SSD_BF16)
         hipLaunchKernelGGL(pack_qkv_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, (const bf16_t*)wq, (const bf16_t*)wk,
-                           (const bf16_t*)wv, (f16_t*)out, d_q, d_kv, d_model, head_dim, 1, scale);
+                           (const bf16_t*)wv, (f16_t*)out, d_q, d_kv, d_model, head_dim, 1, scale, inexact);
     else
         hipLaunchKernelGGL(pack_qkv_kernel<float>, dim3(rows), dim3(256), 0, st, (const float*)wq, (const float*)wk,
-                           (const float*)wv, (float*)out, d_q, d_kv, d_model, head_dim, 0, 1.0f);
+                           (const float*)wv, (float*)out, d_q, d_kv, d_model, head_dim, 0, 1.0f, inexact);
 }
 
 // Fused gate/up: bf16 packs blocks of 64 rows = [32 gate rows | the same 32 up rows]; f32 packs
@@ -304,7 +361,7 @@ void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, 
 template <typename T>
 __global__ void pack_gate_up_kernel(const T* __restrict__ wg, const T* __restrict__ wu,
                                     typename Packed<T>::type* __restrict__ out, int d_ff, int d_model, int interleave,
-                                    float scale) {
+                                    float scale, unsigned long long* __restrict__ inexact) {
     const int p = blockIdx.x;
     const T* src;
     if (interleave) {
@@ -315,17 +372,19 @@ __global__ void pack_gate_up_kernel(const T* __restrict__ wg, const T* __restric
         src = p < d_ff ? wg + (int64_t)p * d_model : wu + (int64_t)(p - d_ff) * d_model;
     }
     typename Packed<T>::type* dst = out + (int64_t)p * d_model;
-    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale);
+    unsigned lost = 0;
+    for (int i = threadIdx.x; i < d_model; i += blockDim.x) dst[i] = Packed<T>::cvt(src[i], scale, lost);
+    add_lost(lost, inexact);
 }
 
 void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
-                         hipStream_t st) {
+                         unsigned long long* inexact, hipStream_t st) {
     if (dtype == SSD_BF16)
         hipLaunchKernelGGL(pack_gate_up_kernel<bf16_t>, dim3(2 * d_ff), dim3(256), 0, st, (const bf16_t*)wg,
-                           (const bf16_t*)wu, (f16_t*)out, d_ff, d_model, 1, scale);
+                           (const bf16_t*)wu, (f16_t*)out, d_ff, d_model, 1, scale, inexact);
     else
         hipLaunchKernelGGL(pack_gate_up_kernel<float>, dim3(2 * d_ff), dim3(256), 0, st, (const float*)wg,
-                           (const float*)wu, (float*)out, d_ff, d_model, 0, 1.0f);
+                           (const float*)wu, (float*)out, d_ff, d_model, 0, 1.0f, inexact);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -88,6 +88,7 @@ struct EpiQkvRope {
     // optional: the table rows already gathered per decoder row (rope_rows[row][i] = rope_tab[pos[row]][i]),
     // which takes the position lookup out of the dependency chain
     const float2* rope_rows;
+    int32_t* flags;                             // sticky device flags: a saturated store raises SSD_FLAG_ACT_OVERFLOW
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert((TN * L::BLOCK) % 64 == 0, "rotation partners live 32 packed columns apart in groups of 64");
@@ -100,6 +101,7 @@ struct EpiQkvRope {
         constexpr int G = residual_batch(TM, 32 / (NJ * L::REGS) > 0 ? 32 / (NJ * L::REGS) : 1);
         const float2* tab = rope_rows ? rope_rows : rope_tab;
         const int d_kv = d_rot - d_q;
+        float peak = 0.f;                                   // largest magnitude stored by this lane
 #pragma unroll
         for (int i0 = 0; i0 < TM; i0 += G) {
             int t_row[G][L::REGS], slot[G][L::REGS];
@@ -123,59 +125,79 @@ struct EpiQkvRope {
                     for (int r = 0; r < L::REGS; ++r)
                         cs[g][jj][r] = p < d_rot ? tab[(int64_t)t_row[g][r] * 64 + i_rot] : make_float2(1.f, 0.f);
                 }
+            // stores of the batch; repeated with clamping by a lane that met a value beyond the half range
+            auto store_batch = [&](auto clamp_c) {
+                constexpr bool CLAMP = decltype(clamp_c)::value;
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+                for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int jj = 0; jj < NJ; ++jj) {
-                    const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
-                    const int p = col0 + j * L::BLOCK;              // packed column of this block
-                    const bool rot = p < d_rot;
-                    const int head = p / 128, i_rot = ((p % 128) / 64) * 32 + p % 32 + lane % L::BLOCK;
-                    const int c0 = rot ? head * 128 + i_rot : p + lane % L::BLOCK;
-                    const int c1 = rot ? c0 + 64 : c0 + 32;
+                    for (int jj = 0; jj < NJ; ++jj) {
+                        const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
+                        const int p = col0 + j * L::BLOCK;              // packed column of this block
+                        const bool rot = p < d_rot;
+                        const int head = p / 128, i_rot = ((p % 128) / 64) * 32 + p % 32 + lane % L::BLOCK;
+                        const int c0 = rot ? head * 128 + i_rot : p + lane % L::BLOCK;
+                        const int c1 = rot ? c0 + 64 : c0 + 32;
 #pragma unroll
-                    for (int r = 0; r < L::REGS; ++r) {
-                        const int row = row0 + L::row(i0 + g, r, lane);
-                        if (row >= M) continue;
-                        const float a = acc[i0 + g][j][r] * descale, b = acc[i0 + g][j + L::PAIR][r] * descale;
-                        const float2 c = cs[g][jj][r];
-                        f16_t* o = qkv + (int64_t)row * ldq;
-                        const f16_t v0 = f32_to_f16(a * c.x - b * c.y), v1 = f32_to_f16(b * c.x + a * c.y);
-                        o[c0] = v0;
-                        o[c1] = v1;
-                        if (slot[g][r] >= 0 && c0 >= d_q) {           // a group of 64 lies inside q, k or v
-                            f16_t* dst = (rot ? kc : vc) + (int64_t)slot[g][r] * d_kv - (rot ? d_q : d_rot);
-                            dst[c0] = v0;
-                            dst[c1] = v1;
+                        for (int r = 0; r < L::REGS; ++r) {
+                            const int row = row0 + L::row(i0 + g, r, lane);
+                            if (row >= M) continue;
+                            const float a = acc[i0 + g][j][r] * descale, b = acc[i0 + g][j + L::PAIR][r] * descale;
+                            const float2 c = cs[g][jj][r];
+                            f16_t* o = qkv + (int64_t)row * ldq;
+                            const f16_t v0 = f16_store<CLAMP>(a * c.x - b * c.y, peak), v1 = f16_store<CLAMP>(b * c.x + a * c.y, peak);
+                            o[c0] = v0;
+                            o[c1] = v1;
+                            if (slot[g][r] >= 0 && c0 >= d_q) {           // a group of 64 lies inside q, k or v
+                                f16_t* dst = (rot ? kc : vc) + (int64_t)slot[g][r] * d_kv - (rot ? d_q : d_rot);
+                                dst[c0] = v0;
+                                dst[c1] = v1;
+                            }
                         }
                     }
-                }
+            };
+            const float before = peak;
+            store_batch(std::false_type());
+            if (!(peak <= F16_MAX)) {
+                peak = before;                              // keep later batches on the plain pass unless they overflow too
+                store_batch(std::true_type());
+                raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
+            }
         }
     }
 };
 
 struct EpiSwiglu {
     static constexpr bool WANTS_SPLIT = false;
-    f16_t* h; int d_ff; float descale;
+    f16_t* h; int d_ff; float descale; int32_t* flags;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert((TN * L::BLOCK) % 64 == 0, "gate/up live 32 packed columns apart in groups of 64");
+        float peak = 0.f;                                   // largest magnitude stored by this lane
+        auto store_all = [&](auto clamp_c) {
+            constexpr bool CLAMP = decltype(clamp_c)::value;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if ((j / L::PAIR) % 2 != 0) continue;
-            const int p = col0 + j * L::BLOCK;
-            const int f = (p / 64) * 32 + p % 32 + lane % L::BLOCK;
+            for (int j = 0; j < TN; ++j) {
+                if ((j / L::PAIR) % 2 != 0) continue;
+                const int p = col0 + j * L::BLOCK;
+                const int f = (p / 64) * 32 + p % 32 + lane % L::BLOCK;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < L::REGS; ++r) {
-                    const int row = row0 + L::row(i, r, lane);
-                    if (row >= M) continue;
-                    const float g = acc[i][j][r] * descale, u = acc[i][j + L::PAIR][r] * descale;
-                    // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division: the epilogue is
-                    // 48 outputs per lane and the division was half of its instructions
-                    h[(int64_t)row * d_ff + f] = f32_to_f16(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
-                }
+                    for (int r = 0; r < L::REGS; ++r) {
+                        const int row = row0 + L::row(i, r, lane);
+                        if (row >= M) continue;
+                        const float g = acc[i][j][r] * descale, u = acc[i][j + L::PAIR][r] * descale;
+                        // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division: the epilogue is
+                        // 48 outputs per lane and the division was half of its instructions
+                        h[(int64_t)row * d_ff + f] = f16_store<CLAMP>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)), peak);
+                    }
+            }
+        };
+        store_all(std::false_type());
+        if (!(peak <= F16_MAX)) {                           // rare: repeat this lane's stores saturated
+            store_all(std::true_type());
+            raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
         }
     }
 };
@@ -353,10 +375,11 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int 
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
-                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, hipStream_t st) {
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, int32_t* flags,
+                          hipStream_t st) {
     const int N = d_q + 2 * d_kv;
     EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q,
-                   reinterpret_cast<const float2*>(rope_rows)};
+                   reinterpret_cast<const float2*>(rope_rows), flags};
     launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
 }
 
@@ -401,8 +424,8 @@ int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_str
 }
 
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
-                        float descale, hipStream_t st) {
-    EpiSwiglu epi{h, d_ff, descale};
+                        float descale, int32_t* flags, hipStream_t st) {
+    EpiSwiglu epi{h, d_ff, descale, flags};
     launch_by_shape(A, Wgu_packed, W_stream, M, 2 * d_ff, K, epi, st);
 }
 

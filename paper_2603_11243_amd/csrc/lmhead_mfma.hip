@@ -221,7 +221,8 @@ void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t*
 __global__ void __launch_bounds__(256) lmhead_finalize_kernel(const float2* __restrict__ part_ms,
                                                               const float* __restrict__ tgt_logit,
                                                               const int2* __restrict__ part_arg, int n_groups, int Mv,
-                                                              float* __restrict__ logp, int32_t* __restrict__ greedy) {
+                                                              float* __restrict__ logp, int32_t* __restrict__ greedy,
+                                                              int32_t* __restrict__ flags) {
     const int lane = threadIdx.x % 64;
     const int row = blockIdx.x * 4 + threadIdx.x / 64;
     if (row >= Mv) return;
@@ -233,7 +234,11 @@ __global__ void __launch_bounds__(256) lmhead_finalize_kernel(const float2* __re
     const float M = group_allreduce<64>(m, OpMax());
     s = (m == -INFINITY) ? 0.f : s * __expf(m - M);
     const float S = group_allreduce<64>(s, OpSum());
-    if (lane == 0) logp[row] = tgt_logit[row] - (M + logf(S));
+    if (lane == 0) {
+        const float lp = tgt_logit[row] - (M + logf(S));
+        logp[row] = lp;
+        if (!(fabsf(lp) < INFINITY)) raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);     // non-finite likelihood: inputs were not finite
+    }
     if (greedy) {
         int cand = 0x7fffffff;
         for (int g = lane; g < n_groups; g += 64) {
@@ -246,10 +251,10 @@ __global__ void __launch_bounds__(256) lmhead_finalize_kernel(const float2* __re
 }
 
 void launch_lmhead_finalize(const float2* part_ms, const float* tgt_logit, const int2* part_arg, int n_groups, int Mv,
-                            float* logp, int32_t* greedy, hipStream_t st) {
+                            float* logp, int32_t* greedy, int32_t* flags, hipStream_t st) {
     if (Mv <= 0) return;
     hipLaunchKernelGGL(lmhead_finalize_kernel, dim3((Mv + 3) / 4), dim3(256), 0, st, part_ms, tgt_logit, part_arg,
-                       n_groups, Mv, logp, greedy);
+                       n_groups, Mv, logp, greedy, flags);
 }
 
 }  // namespace ssd

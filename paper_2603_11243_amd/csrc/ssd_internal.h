@@ -46,16 +46,20 @@ struct AttnTile {
 };
 
 // ---- elementwise.hip
-// flags (may be NULL): *flags = SSD_FLAG_TOKEN_CLAMPED if a token id had to be clamped into [0, vocab)
+// flags (may be NULL): SSD_FLAG_TOKEN_CLAMPED is raised if a token id had to be clamped into [0, vocab)
 void launch_embed_rows(int dtype, const void* speech_emb, const void* embed, const int32_t* prompt_ids,
                        const int32_t* draft_ids, const int32_t* row_src, int M, int d, int vocab, float* x,
                        int32_t* flags, hipStream_t st);
 void launch_gather_rows(const void* src, const int32_t* row_idx, int n_rows, int64_t row_bytes, void* dst, hipStream_t st);
+// out[i] = src[idx[i]], passed through table (clamped into [0, n_table)) when table is not NULL
+void launch_gather_ids(const int32_t* src, const int32_t* idx, int n, const int32_t* table, int n_table, int32_t* out, hipStream_t st);
 // a = rmsnorm(x) * gain;  rows optionally gathered through row_idx (NULL = identity).
 // If n_splits > 1, x[row] is first increased by partials[s][row] for s = 0..n_splits-1 (fixed order;
 // partials is [n_splits][M][d] fp32) and, when row_idx is NULL, written back.
+// flags (may be NULL): SSD_FLAG_ACT_OVERFLOW is raised when a half-precision output had to be saturated
 void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d,
-                    float eps, void* out, const float* partials, int n_splits, int64_t split_stride, hipStream_t st);
+                    float eps, void* out, const float* partials, int n_splits, int64_t split_stride, int32_t* flags,
+                    hipStream_t st);
 
 // ---- f32_path.hip (all-fp32 decoder for the tiny configuration)
 enum F32Epilogue { F32_STORE = 0, F32_ADD = 1 };
@@ -77,7 +81,8 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 // rope_rows (may be NULL): rope_tab[pos[row]] gathered per row, [M][64] (cos, sin); read instead of pos and rope_tab
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
-                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, hipStream_t st);
+                          const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, int32_t* flags,
+                          hipStream_t st);
 constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
 constexpr int SKINNY_MAX_SPLITS = 8;
 int gemm_residual_splits(int M, int N, int K, bool have_stream);
@@ -85,7 +90,7 @@ int gemm_residual_splits(int M, int N, int K, bool have_stream);
 int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
                          float descale, hipStream_t st);
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
-                        float descale, hipStream_t st);
+                        float descale, int32_t* flags, hipStream_t st);
 // second copy of an f16 weight matrix W[N,K] for the few-row kernel (N % 64 == 0, K % 256 == 0)
 bool stream_layout_supported(int N, int K);
 void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_t st);
@@ -96,17 +101,20 @@ int lmhead_col_groups(int vocab);
 void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d,
                         int vocab, float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy,
                         float descale, hipStream_t st);
+// flags (may be NULL): SSD_FLAG_ACT_OVERFLOW is raised when a log-likelihood is not finite
 void launch_lmhead_finalize(const float2* part_ms, const float* tgt_logit, const int2* part_arg, int n_groups,
-                            int Mv, float* logp, int32_t* greedy, hipStream_t st);
+                            int Mv, float* logp, int32_t* greedy, int32_t* flags, hipStream_t st);
 
 // weight re-layout at context creation
 // (bf16 weights are converted to f16 times the power of two `scale`; fp32 weights are copied)
 void launch_absmax(int dtype, const void* w, int64_t n, unsigned int* out_bits, hipStream_t st);
-void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, hipStream_t st);
+// inexact (device counter, may be NULL) is increased by the number of values whose half representation is not exact
+void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, unsigned long long* inexact,
+                           hipStream_t st);
 void launch_pack_qkv(int dtype, const void* wq, const void* wk, const void* wv, void* out, int d_q, int d_kv,
-                     int d_model, int head_dim, float scale, hipStream_t st);
+                     int d_model, int head_dim, float scale, unsigned long long* inexact, hipStream_t st);
 void launch_pack_gate_up(int dtype, const void* wg, const void* wu, void* out, int d_ff, int d_model, float scale,
-                         hipStream_t st);
+                         unsigned long long* inexact, hipStream_t st);
 
 // ---- ar_decode.hip (auto-regressive fallback): K/V cache of one layer is K [slots, d_kv], V [slots, d_kv]
 // in the activation type (IEEE half for bf16-stored models, fp32 otherwise); row_slot < 0 skips a row
@@ -123,7 +131,7 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
 // cached rows plus the new one.
 void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
                               const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
-                              void* out, hipStream_t st);
+                              void* out, int32_t* flags, hipStream_t st);
 // QKV projection left as K-split partial sums for launch_decode_attn_fused; returns the split count, or 0 if
 // the shape is not served (then nothing was launched)
 int launch_gemm_qkv_partial(const uint16_t* A, const void* W_stream, float* part, int M, int d_model, int N, float descale,

@@ -131,10 +131,13 @@ def test_ar_fallback_bf16_reduced_depth(name, layers, B, n_steps):
     assert n_exact >= (n_steps + 1) * len(res[1]) // 2
 
 
-def test_ar_fallback_bf16_full_size_sampled_utterances():
-    """The configuration bench.py times (ragged batch of 64 on the full 24-layer 1B-class decoder): the whole chain on
-    the GPU, the oracle's continuation for the two shortest rejected utterances."""
-    wl = WORKLOADS["cfg3_1b_ragged64"]
+@pytest.mark.parametrize("name", ["cfg3_1b_ragged64", "cfg4_1b_long_ml"])
+def test_ar_fallback_bf16_full_size_sampled_utterances(name):
+    """Full 24-layer 1B-class decoder, whole batch on the GPU: the ragged batch of 64 (contexts up to about 200 rows)
+    and the long-form batch (every context beyond 256 rows, so that each wavefront of the decode attention walks more
+    than one block of keys).  The oracle continues the rejected utterance with the shortest and the one with the
+    longest context."""
+    wl = WORKLOADS[name]
     cb = make_ctc_batch(wl)
     fail, drafts = _gate_drafts(wl, cb)
     vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
@@ -144,8 +147,11 @@ def test_ar_fallback_bf16_full_size_sampled_utterances():
     res = _run_chain(wl, w, vi, tau, n_steps)
     rej = res[1]
     assert 1 <= len(rej) <= 32                     # the few-row path of the step, as in the benchmark
-    n = np.diff(vi.cu_speech) + np.diff(vi.cu_prompt) + np.diff(vi.cu_draft)
-    sample = np.argsort(n[rej])[:2]
+    ctx_len = (np.diff(vi.cu_speech) + np.diff(vi.cu_prompt))[rej] + res[0][rej]
+    by_ctx = np.argsort(ctx_len, kind="stable")
+    sample = sorted({int(by_ctx[0]), int(by_ctx[-1])})
+    if name == "cfg4_1b_long_ml":
+        assert ctx_len[by_ctx[-1]] > 256
     n_exact = _check_against_oracle(wl, w, vi, tau, n_steps, *res, sample=sample)
     print(f"{wl.name}: {n_exact} of {(n_steps + 1) * len(sample)} generated tokens identical to the oracle's")
     assert n_exact >= (n_steps + 1) * len(sample) // 2

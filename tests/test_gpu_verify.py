@@ -59,8 +59,9 @@ def _subset(vi, idx):
                         cu([vi.cu_draft[b + 1] - vi.cu_draft[b] for b in idx]))
 
 
-def _compare(wl, weights, vi, res, tau, sample=None):
-    tol = TOL_LOGP[wl.model.dtype]
+def _compare(wl, weights, vi, res, tau, sample=None, tol=None, stats=None):
+    """stats (dict, optional) receives the largest relative L2 error of a final-normed hidden row."""
+    tol = TOL_LOGP[wl.model.dtype] if tol is None else tol
     idx = list(range(len(vi.cu_draft) - 1)) if sample is None else list(sample)
     sub = _subset(vi, idx)
     lp, hid, greedy = O.draft_logp(weights, wl.model, sub.speech_emb, sub.cu_speech, sub.prompt_ids, sub.cu_prompt,
@@ -75,6 +76,9 @@ def _compare(wl, weights, vi, res, tau, sample=None):
         worst = max(worst, err)
         assert err <= tol, f"utt {b}: |logp - oracle| = {err:.3e} > {tol}"
         check_accept_len(res["accept_len"][b], res["all_accepted"][b], lp[k], tau, tol)
+        if stats is not None and hi > lo:
+            dh = np.linalg.norm(res["h_verify"][lo:hi] - hid[k], axis=1) / np.linalg.norm(hid[k], axis=1)
+            stats["hidden_rel_err"] = max(stats.get("hidden_rel_err", 0.0), float(dh.max()))
         if "greedy_tok" in res and hi > lo:
             mism = np.flatnonzero(res["greedy_tok"][lo:hi] != greedy[k])
             if len(mism):                      # only legal when the oracle's top two logits are within tolerance
@@ -99,7 +103,8 @@ def test_cfg1_tiny_f32_full_chain():
     res = _run_gpu(wl, w, vi, tau)
     worst = _compare(wl, w, vi, res, tau)
     print(f"cfg1 worst |dlogp| = {worst:.3e}")
-    assert len(set(res["accept_len"].tolist())) > 1 or True
+    # the threshold sits inside the spread of this model's likelihoods: prefixes of different length occur
+    assert 0 < res["accept_len"].sum() < vi.cu_draft[-1]
 
 
 def test_tiny_f32_sharper_model_and_edge_shapes():
@@ -290,11 +295,13 @@ def test_bf16_empty_drafts_and_single_row_utterances():
 
 # ------------------------------------------------------------------ bf16, full depth, sampled utterances
 
-@pytest.mark.parametrize("name,n_sample", [("cfg2_1b_b1", 1), ("cfg3_1b_ragged64", 2), ("cfg4_1b_long_ml", 1),
-                                           ("cfg5_3b_ragged128", 2)])
-def test_bf16_full_size_sampled_utterances(name, n_sample):
-    """The whole batch runs on the GPU in the benchmark's launch configuration; the oracle scores a
-    seeded sample of utterances (utterances are independent, so their results do not depend on the batch)."""
+@pytest.mark.parametrize("name,n_random", [("cfg2_1b_b1", None), ("cfg3_1b_ragged64", None), ("cfg4_1b_long_ml", None),
+                                           ("cfg5_3b_ragged128", 4)])
+def test_bf16_full_size_against_oracle(name, n_random):
+    """The whole batch runs on the GPU in the benchmark's launch configuration.  The oracle scores every verified
+    utterance of the three 1B-class configurations; of the 3B-class one (90 utterances, 32 layers) it scores the
+    longest, the shortest, n_random seeded random ones and the two whose GPU likelihoods come closest to the
+    threshold (utterances are independent, so their results do not depend on the rest of the batch)."""
     wl = WORKLOADS[name]
     cb = make_ctc_batch(wl)
     fail, drafts = _gate_drafts(wl, cb)
@@ -303,13 +310,21 @@ def test_bf16_full_size_sampled_utterances(name, n_sample):
     tau = _tau_for(wl)
     res = _run_gpu(wl, w, vi, tau)
     assert np.isfinite(res["draft_logp"]).all()
-    rng = np.random.default_rng(wl.seed)
     lens = np.diff(vi.cu_speech) + np.diff(vi.cu_prompt) + np.diff(vi.cu_draft)
-    order = np.argsort(lens)
-    sample = sorted(set([int(order[0])] + [int(x) for x in rng.choice(len(lens), size=n_sample - 1, replace=False)]
-                        if n_sample > 1 else [int(order[len(order) // 2])]))
+    Bv = len(lens)
+    if n_random is None:
+        sample = list(range(Bv))
+    else:
+        rng = np.random.default_rng(wl.seed)
+        order = np.argsort(lens, kind="stable")
+        margin = np.array([np.abs(res["draft_logp"][vi.cu_draft[b]:vi.cu_draft[b + 1]] - np.log(tau)).min()
+                           if vi.cu_draft[b + 1] > vi.cu_draft[b] else np.inf for b in range(Bv)])
+        sample = sorted(set([int(order[-1]), int(order[0])] + [int(x) for x in np.argsort(margin)[:2]]
+                            + [int(x) for x in rng.choice(Bv, size=n_random, replace=False)]))
+        assert int(order[-1]) in sample and lens[order[-1]] == lens.max()
     worst = _compare(wl, w, vi, res, tau, sample=sample)
-    print(f"{name}: worst |dlogp| = {worst:.3e} on utterances {sample}")
+    print(f"{name}: worst |dlogp| = {worst:.3e} on {len(sample)} of {Bv} utterances "
+          f"({int(sum(lens[b] for b in sample))} of {int(lens.sum())} rows, longest {int(lens.max())})")
     # properties that hold at any size: accepted prefix is consistent with the GPU's own scores
     ln_tau = np.float32(np.log(np.float64(np.float32(tau))))
     for b in range(len(vi.cu_draft) - 1):
@@ -318,3 +333,128 @@ def test_bf16_full_size_sampled_utterances(name, n_sample):
         want = int(bad[0]) if len(bad) else len(lp)
         assert res["accept_len"][b] == want and res["all_accepted"][b] == (want == len(lp))
         assert (lp <= 0).all()
+
+
+# ------------------------------------------------------------------ bf16, hard inputs for the half-precision operands
+
+def _sharp_weights(m, seed):
+    """Projection matrices 4x, LM head 8x the usual scale: attention scores with a spread of about 13
+    (peaked attention), logits with a spread of about 7 (peaked output distribution), residual rows in the tens to
+    hundreds after a few layers."""
+    w = make_model_weights(m, seed, device="cuda")
+    for L in w["layers"]:
+        for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            L[k] = (L[k].float() * 4).to(torch.bfloat16)
+    w["lm_head"] = (w["lm_head"].float() * 8).to(torch.bfloat16)
+    return w
+
+
+@pytest.mark.parametrize("layers", [1, 3])
+def test_bf16_sharper_model(layers):
+    from workloads.synth import VerifyInputs
+    wl = replace(scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=layers, B=6), gate_rate=0.0)
+    w = _sharp_weights(wl.model, 31 + layers)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    vi = VerifyInputs((vi.speech_emb.float() * 25).to(torch.bfloat16), vi.cu_speech, vi.prompt_ids, vi.cu_prompt,
+                      vi.draft_ids, vi.cu_draft)
+    tau = float(np.exp(-np.log(wl.model.vocab) - 30.0))        # inside the (wide) spread of these likelihoods
+    from paper_2603_11243_amd.binding import Context
+    ctx = Context(wl.model, w)
+    assert ctx.inexact_weights() == 0
+    ctx.close()
+    res = _run_gpu(wl, w, vi, tau)
+    # What the 16-bit operands cost here: attention scores of magnitude up to ~40 formed from q and k rounded to 11
+    # significant bits carry an absolute error of about 5e-3, i.e. 0.5 % on a softmax weight, and a hidden row ends
+    # up 4e-3 (one layer) to 1e-2 (three layers) off in relative terms.  That error reaches log p multiplied by the
+    # spread of the logits, which the 8x LM head makes 8 times that of the five configurations (0.16 sqrt(d) = 7.2
+    # against 0.9).  So the likelihood tolerance is 10 x the 2e-2 of those configurations, and the hidden rows
+    # themselves are held to a relative error of 2e-2; a dropped tile or a wrong scale would be O(1) in both.
+    stats = {}
+    worst = _compare(wl, w, vi, res, tau, tol=10 * TOL_LOGP["bf16"], stats=stats)
+    spread = float(np.std(res["draft_logp"]))
+    print(f"sharp model, {layers} layer(s): worst |dlogp| = {worst:.3e}, spread of log p = {spread:.2f}, "
+          f"worst relative error of a hidden row = {stats['hidden_rel_err']:.2e}")
+    assert spread > 3.0                      # the output distribution really is peaked
+    assert stats["hidden_rel_err"] < 2e-2
+
+
+def test_bf16_activation_overflow_is_saturated_and_flagged():
+    """Gate and up projections scaled until SiLU(gate) * up leaves the half range: the store saturates, the
+    sticky flag is raised once, every output stays finite; the unscaled model raises nothing."""
+    from paper_2603_11243_amd.binding import Context
+    wl = replace(scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=1, B=3), gate_rate=0.0)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    p_ids, d_ids = _dev(vi.prompt_ids), _dev(vi.draft_ids)
+    M = int(vi.cu_speech[-1] + vi.cu_prompt[-1] + vi.cu_draft[-1])
+    for scale, want in ((1.0, 0), (512.0, 2)):
+        w = make_model_weights(wl.model, 17, device="cuda")
+        for k in ("w_gate", "w_up"):
+            w["layers"][0][k] = (w["layers"][0][k].float() * scale).to(torch.bfloat16)
+        ctx = Context(wl.model, w)
+        try:
+            ctx.reserve(max_tokens=M, max_verify_rows=int(vi.cu_draft[-1]), max_utts=len(vi.cu_draft) - 1)
+            hv = ctx.verify_forward(vi.speech_emb, vi.cu_speech, p_ids, vi.cu_prompt, d_ids, vi.cu_draft)
+            out = ctx.accept_prefix(hv, d_ids, vi.cu_draft, 1e-6)
+            flags = ctx.device_flags()
+            assert flags == want, f"scale {scale}: flags {flags}"
+            assert ctx.device_flags() == 0                       # reported once, then cleared
+            assert torch.isfinite(hv.float()).all() and torch.isfinite(out["draft_logp"]).all()
+        finally:
+            ctx.close()
+
+
+def test_bf16_causality_and_batch_isolation():
+    """bf16 path, two 1B-width layers.  Changing a later draft token leaves every earlier score bit-identical (same
+    launch shapes, causal mask); an utterance scored alone agrees with its scores inside the batch (not bitwise: the
+    last layer of a small batch takes the few-row kernels, which sum K in a different order)."""
+    wl = replace(scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=2, B=6), gate_rate=0.0)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, 23, device="cuda")
+    tau = _tau_for(wl)
+    base = _run_gpu(wl, w, vi, tau, want_greedy=False)
+    b = int(np.argmax(np.diff(vi.cu_draft)))
+    lo, hi = vi.cu_draft[b], vi.cu_draft[b + 1]
+    k = (hi - lo) // 2
+    vi2 = _subset(vi, list(range(len(vi.cu_draft) - 1)))
+    vi2.draft_ids[lo + k] = (vi2.draft_ids[lo + k] + 1) % wl.model.vocab
+    mod = _run_gpu(wl, w, vi2, tau, want_greedy=False)
+    assert np.array_equal(mod["draft_logp"][:lo + k], base["draft_logp"][:lo + k])
+    assert np.array_equal(mod["draft_logp"][hi:], base["draft_logp"][hi:])
+    assert mod["draft_logp"][lo + k] != base["draft_logp"][lo + k]
+    alone = _run_gpu(wl, w, _subset(vi, [b]), tau, want_greedy=False)
+    assert np.abs(alone["draft_logp"] - base["draft_logp"][lo:hi]).max() < 2e-3
+
+
+def test_sizes_beyond_32_bit_offsets_and_odd_head_dim_are_refused():
+    """Host-side refusals that need a context with a model: an activation matrix of 4 GiB or more (the GEMM
+    loaders use 32-bit byte offsets), and the AR fallback with a head_dim that is not a multiple of 8."""
+    from paper_2603_11243_amd.binding import Context, SsdError
+    wl = WORKLOADS["cfg1_tiny_f32"]
+    ctx = Context(wl.model, make_model_weights(wl.model, 5))
+    try:
+        ctx.reserve(max_tokens=64, max_verify_rows=8, max_utts=2)
+        n = 1100                                  # 1100 utterances x 1000 rows x d_ff 1024 x 4 bytes >= 4 GiB
+        cu_s = (np.arange(n + 1) * 1000).astype(np.int32)
+        zero = np.zeros(n + 1, np.int32)
+        fake = torch.zeros(16, device="cuda")
+        with pytest.raises(SsdError, match="4 GiB") as ei:
+            ctx._check(ctx._lib.verify_forward(ctx._h, fake.data_ptr(), cu_s.ctypes.data, None, zero.ctypes.data, None,
+                                               zero.ctypes.data, n, None))
+        assert ei.value.code == -2
+    finally:
+        ctx.close()
+    m = replace(wl.model, head_dim=12)            # 4 heads x 12: legal for verify_forward, not for the decode attention
+    ctx = Context(m, make_model_weights(m, 6))
+    try:
+        ctx.set_kv_cache(64)
+        ctx.reserve(max_tokens=64, max_verify_rows=8, max_utts=2, ar_utts=1, ar_steps=2)
+        with pytest.raises(SsdError, match="multiple of 8"):
+            ctx.ar_fallback([0], [5], _dev([1]), 2)
+    finally:
+        ctx.close()
