@@ -46,15 +46,21 @@ enum ssd_status {
 };
 
 enum ssd_dtype { SSD_F32 = 0, SSD_BF16 = 1 };
+/* Matrix-core operand type of an SSD_BF16 model (the paper's stack runs in bfloat16, Sec. 3.2).
+ *   SSD_OP_F16  (default) activations are rounded to IEEE half (11 significant bits) where they enter a
+ *               contraction; the bf16 weights are converted once to half times a per-tensor power of two
+ *               (exact for every value within 31 binades of the tensor's largest; ssd_inexact_weights
+ *               counts the rest).  Range 65504: stores saturate and raise SSD_FLAG_ACT_OVERFLOW.
+ *   SSD_OP_BF16 activations are rounded to bfloat16 (8 significant bits, the range of fp32), the stored
+ *               weights are the operands.  Same kernels and MFMA rate; about 8 times the rounding error. */
+enum ssd_operand { SSD_OP_F16 = 0, SSD_OP_BF16 = 1 };
 
 /* Decoder-only LLM: pre-norm RMSNorm, grouped-query causal attention with half-split rotary
  * embedding (component i paired with i + head_dim/2), SwiGLU MLP, no biases.
  * dtype is the storage type of every weight and of speech_emb.  SSD_F32 is all fp32.  SSD_BF16
  * runs the contractions on the 16-bit matrix cores with fp32 accumulation and an fp32 residual
- * stream; the matrix-core operand type is IEEE half: activations are rounded to half (11
- * significant bits instead of bf16's 8, same MFMA rate) and the bf16 weights are converted once,
- * exactly, to half times a per-tensor power of two.  Activations beyond the half range (|v| >
- * 65504 after RMSNorm or in the MLP) are not supported.
+ * stream; the matrix-core operand type is chosen with `operand` (enum ssd_operand): IEEE half by
+ * default, bfloat16 on request.
  * Supported: head_dim 128 (bf16) or any multiple of 4 up to 128 (f32); n_q_heads a multiple of
  * n_kv_heads (at most 4 times for bf16); for bf16 d_model (<= 8192), (n_q_heads + 2 n_kv_heads)*head_dim
  * and vocab multiples of 256, d_ff a multiple of 128; for f32 d_model, d_ff, n_q_heads*head_dim multiples of 16 and d_model <= 1024. */
@@ -63,6 +69,7 @@ typedef struct {
     float   rms_eps, rope_theta;
     int32_t dtype;            /* enum ssd_dtype */
     int32_t max_positions;    /* longest sequence (speech + prompt + draft rows of one utterance) */
+    int32_t operand;          /* enum ssd_operand; ignored for SSD_F32 unless SSD_OP_BF16 (rejected) */
 } ssd_model_cfg;
 
 /* All matrices are row-major [out_features, in_features] (y = W x); per-layer members are HOST
@@ -241,8 +248,9 @@ int ssd_gather_i32(ssd_ctx *ctx, const int32_t *src /*dev*/, const int32_t *idx 
  * hidden row of sequence index S + P + i - 2 (the position whose next-token distribution scores
  * token i) to h_verify row cu_draft[b] + i - 1.  An utterance needs S + P >= 1; U = 0 is legal.
  * speech_emb: dev [cu_speech[Bv], d_model]; prompt_ids / draft_ids: dev int32 LLM token ids
- * (ids outside [0, vocab) are clamped on the device); h_verify: dev [cu_draft[Bv], d_model], IEEE half
- * for SSD_BF16 models and fp32 for SSD_F32: an activation buffer that accept_prefix consumes.
+ * (ids outside [0, vocab) are clamped on the device); h_verify: dev [cu_draft[Bv], d_model], in the operand
+ * type for SSD_BF16 models (IEEE half or bfloat16) and fp32 for SSD_F32: an activation buffer that
+ * accept_prefix consumes.
  * SSD_ESHAPE if an activation matrix of the call (rows x max(d_ff, q+k+v width, d_model) elements) would
  * reach 4 GiB: split the batch. */
 int verify_forward(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_speech /*host*/,
@@ -261,8 +269,8 @@ int verify_forward_kv(ssd_ctx *ctx, const void *speech_emb, const int32_t *cu_sp
                       const int32_t *kv_start /*host*/, void *h_verify);
 
 /* K/V cache for the auto-regressive fallback: a caller-owned dev buffer, 256-byte aligned, holding
- * for every layer K [slots, n_kv_heads*head_dim] and V [slots, ...] in the activation type (IEEE half
- * for SSD_BF16 models, fp32 for SSD_F32).  A NULL pointer detaches the cache. */
+ * for every layer K [slots, n_kv_heads*head_dim] and V [slots, ...] in the activation type (the operand
+ * type for SSD_BF16 models, fp32 for SSD_F32).  A NULL pointer detaches the cache. */
 size_t ssd_kv_cache_bytes(const ssd_ctx *ctx, int64_t slots);
 int ssd_set_kv_cache(ssd_ctx *ctx, void *dev_ptr, size_t bytes, int64_t slots);
 

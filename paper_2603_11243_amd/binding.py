@@ -38,7 +38,7 @@ class ModelCfgC(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
-                ("max_positions", C.c_int32)]
+                ("max_positions", C.c_int32), ("operand", C.c_int32)]
 
 
 class WeightsC(C.Structure):
@@ -136,7 +136,7 @@ class Context:
     """Owns one ssd_ctx.  `weights` is the dict layout of workloads.make_model_weights (device tensors)."""
 
     def __init__(self, model_cfg=None, weights: Optional[dict] = None, device="cuda:0", stream=None,
-                 max_positions: int = 1024):
+                 max_positions: int = 1024, operand: str = "f16"):
         self._lib = lib()
         self.device = torch.device(device)
         self.cfg = model_cfg
@@ -150,11 +150,13 @@ class Context:
         if model_cfg is not None:
             m = model_cfg
             self.dtype = {"bf16": torch.bfloat16, "f32": torch.float32}[m.dtype]
-            # h_verify is an activation buffer between verify_forward and accept_prefix: IEEE half for
-            # bf16-stored models (the MFMA operand type), fp32 otherwise
-            self.act_dtype = {"bf16": torch.float16, "f32": torch.float32}[m.dtype]
+            # h_verify is an activation buffer between verify_forward and accept_prefix: the MFMA operand type for
+            # bf16-stored models (IEEE half by default, bfloat16 with operand="bf16"), fp32 otherwise
+            self.operand = operand
+            self.act_dtype = torch.float32 if m.dtype == "f32" else {"f16": torch.float16, "bf16": torch.bfloat16}[operand]
             cfg_c = ModelCfgC(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ff, m.vocab,
-                              m.rms_eps, m.rope_theta, _DTYPE_CODE[self.dtype], max_positions)
+                              m.rms_eps, m.rope_theta, _DTYPE_CODE[self.dtype], max_positions,
+                              {"f16": 0, "bf16": 1}[operand])
             w_c = WeightsC()
 
             def dev(t):

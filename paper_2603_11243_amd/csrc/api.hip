@@ -79,6 +79,7 @@ struct Profiler {
 struct ssd_ctx {
     hipStream_t stream = nullptr;
     bool has_model = false;
+    bool bf16_ops = false;                   // matrix-core operand type of a 16-bit model: bfloat16 instead of IEEE half
     ssd_model_cfg cfg{};
     const void* embed = nullptr;
     const void* lm_head = nullptr;
@@ -257,6 +258,8 @@ int check_model(ssd_ctx* c, const ssd_model_cfg& m) {
     } else {
         return fail(c, SSD_EUNSUPPORTED, "ssd_create: dtype %d", m.dtype);
     }
+    if (m.operand != SSD_OP_F16 && m.operand != SSD_OP_BF16) return fail(c, SSD_EUNSUPPORTED, "ssd_create: operand type %d", m.operand);
+    if (m.operand == SSD_OP_BF16 && m.dtype != SSD_BF16) return fail(c, SSD_EUNSUPPORTED, "ssd_create: bfloat16 operands need dtype SSD_BF16");
     return SSD_OK;
 }
 
@@ -289,7 +292,9 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
     c->embed = w->embed; c->lm_head = w->lm_head; c->norm_final = w->norm_final;
     const int L = cfg->n_layers, d = cfg->d_model, dq = cfg->n_q_heads * cfg->head_dim, dkv = cfg->n_kv_heads * cfg->head_dim;
     const int dff = cfg->d_ff;
-    const bool half = cfg->dtype == SSD_BF16;
+    const bool half = cfg->dtype == SSD_BF16;                // a 16-bit model (either operand type)
+    const bool bf = half && cfg->operand == SSD_OP_BF16;     // bfloat16 operands: the stored weights are the operands
+    c->bf16_ops = bf;
     const size_t es = elem_size(cfg->dtype);
     auto bail = [&](hipError_t e, const char* what) {
         fprintf(stderr, "ssd_create: %s: %s\n", what, hipGetErrorString(e));
@@ -305,7 +310,7 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
     // largest magnitude of each weight group -> exact power-of-two scale into the f16 range
     const int n_groups = 4 * L + 1;
     std::vector<float> scale(n_groups, 1.0f);
-    if (half) {
+    if (half && !bf) {
         unsigned int* d_max = nullptr;
         if ((e = dev_alloc((void**)&d_max, (size_t)n_groups * 4)) != hipSuccess) return bail(e, "hipMalloc(absmax)");
         if ((e = hipMemsetAsync(d_max, 0, (size_t)n_groups * 4, c->stream)) != hipSuccess) return bail(e, "hipMemsetAsync");
@@ -341,14 +346,14 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
         c->wqkv.push_back(pq);
         if ((e = dev_alloc(&pg, (size_t)2 * dff * d * es)) != hipSuccess) return bail(e, "hipMalloc(wgu)");
         c->wgu.push_back(pg);
-        launch_pack_qkv(cfg->dtype, w->wq[l], w->wk[l], w->wv[l], pq, dq, dkv, d, cfg->head_dim, scale[4 * l + 0], d_inexact, c->stream);
-        launch_pack_gate_up(cfg->dtype, w->w_gate[l], w->w_up[l], pg, dff, d, scale[4 * l + 2], d_inexact, c->stream);
+        launch_pack_qkv(cfg->dtype, w->wq[l], w->wk[l], w->wv[l], pq, dq, dkv, d, cfg->head_dim, bf ? 0.f : scale[4 * l + 0], d_inexact, c->stream);
+        launch_pack_gate_up(cfg->dtype, w->w_gate[l], w->w_up[l], pg, dff, d, bf ? 0.f : scale[4 * l + 2], d_inexact, c->stream);
         if (half) {
             void *po = nullptr, *pd = nullptr;
             if ((e = dev_alloc(&po, (size_t)d * dq * 2)) != hipSuccess) return bail(e, "hipMalloc(wo)");
             if ((e = dev_alloc(&pd, (size_t)d * dff * 2)) != hipSuccess) return bail(e, "hipMalloc(w_down)");
-            launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, scale[4 * l + 1], d_inexact, c->stream);
-            launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, scale[4 * l + 3], d_inexact, c->stream);
+            launch_convert_weight(cfg->dtype, w->wo[l], po, d, dq, bf ? 0.f : scale[4 * l + 1], d_inexact, c->stream);
+            launch_convert_weight(cfg->dtype, w->w_down[l], pd, d, dff, bf ? 0.f : scale[4 * l + 3], d_inexact, c->stream);
             c->wo.push_back(po); c->w_down.push_back(pd);
             struct { const void* src; int N, K; std::vector<void*>* dst; } copies[4] = {
                 {pq, dq + 2 * dkv, d, &c->s_qkv}, {po, d, dq, &c->s_o}, {pg, 2 * dff, d, &c->s_gu}, {pd, d, dff, &c->s_down}};
@@ -369,7 +374,7 @@ int ssd_create(ssd_ctx** out, const ssd_model_cfg* cfg, const ssd_weights* w, vo
     if (half) {
         void* pl = nullptr;
         if ((e = dev_alloc(&pl, (size_t)cfg->vocab * d * 2)) != hipSuccess) return bail(e, "hipMalloc(lm_head)");
-        launch_convert_weight(cfg->dtype, w->lm_head, pl, cfg->vocab, d, scale[4 * L], d_inexact, c->stream);
+        launch_convert_weight(cfg->dtype, w->lm_head, pl, cfg->vocab, d, bf ? 0.f : scale[4 * L], d_inexact, c->stream);
         c->lm_head = pl;
         c->ds_lm = 1.0f / scale[4 * L];
     }
@@ -854,12 +859,12 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     const int Mvi = (int)Mv;
     bool compact = false;
     for (int l = 0; l < m.n_layers; ++l) {
-        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st); }
+        { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Mi, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, ctx->bf16_ops, st); }
         pending = 1;
         if (m.dtype == SSD_BF16) {
             { ProfScope ps(ctx, SSD_PROF_GEMM_QKV); launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Mi, d, dq, dkv, ctx->ds_qkv[l],
-                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, rope_rows, ctx->dev_flags, st); }
-            { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, st); }
+                                                                         kv_start ? d_row_slot : nullptr, kv_start ? (uint16_t*)kv_k(ctx, l) : nullptr, kv_start ? (uint16_t*)kv_v(ctx, l) : nullptr, rope_rows, ctx->dev_flags, ctx->bf16_ops, st); }
+            { ProfScope ps(ctx, SSD_PROF_ATTN); launch_attn_mfma((const uint16_t*)qkv, (uint16_t*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, ctx->bf16_ops, st); }
             float* xr = x; const void* attr = att; int rows = Mi;
             if (l == m.n_layers - 1) {
                 ProfScope ps(ctx, SSD_PROF_OTHER);
@@ -868,11 +873,11 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
                 xr = x_c; attr = att_c; rows = Mvi; compact = true;
             }
             const int64_t stride = (int64_t)rows * d;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], ctx->s_o[l], xr, partials, rows, d, dq, ctx->ds_o[l], st); }
-            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, ctx->dev_flags, st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_O); pending = launch_gemm_residual((const uint16_t*)attr, (const uint16_t*)ctx->wo[l], ctx->s_o[l], xr, partials, rows, d, dq, ctx->ds_o[l], ctx->bf16_ops, st); }
+            { ProfScope ps(ctx, SSD_PROF_OTHER); launch_rmsnorm(m.dtype, xr, ctx->norm_mlp[l], nullptr, rows, d, m.rms_eps, a, partials, pending, stride, ctx->dev_flags, ctx->bf16_ops, st); }
             pending = 1;
-            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, st); }
-            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_GATE_UP); launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, rows, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, ctx->bf16_ops, st); }
+            { ProfScope ps(ctx, SSD_PROF_GEMM_DOWN); pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], xr, partials, rows, d, m.d_ff, ctx->ds_down[l], ctx->bf16_ops, st); }
         } else {
             float* gu = reinterpret_cast<float*>(ws + p.gu);
             launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Mi, dq + 2 * dkv, d, F32_STORE, st);
@@ -880,7 +885,7 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
             if (kv_start) launch_kv_store(m.dtype, qkv, d_row_slot, Mi, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
             launch_attn_f32((const float*)qkv, (float*)att, d_tiles, n_tiles, m.n_q_heads, m.n_kv_heads, m.head_dim, st);
             launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Mi, d, dq, F32_ADD, st);
-            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Mi, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, ctx->bf16_ops, st);
             launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Mi, 2 * m.d_ff, d, F32_STORE, st);
             launch_swiglu_f32(gu, (float*)h, Mi, m.d_ff, st);
             launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Mi, d, m.d_ff, F32_ADD, st);
@@ -889,10 +894,10 @@ int verify_impl(ssd_ctx* ctx, const void* speech_emb, const int32_t* cu_speech, 
     // final RMSNorm of the positions that score a draft token
     if (compact) {
         ProfScope ps(ctx, SSD_PROF_OTHER);
-        launch_rmsnorm(m.dtype, x_c, ctx->norm_final, nullptr, Mvi, d, m.rms_eps, h_verify, partials, pending, (int64_t)Mvi * d, ctx->dev_flags, st);
+        launch_rmsnorm(m.dtype, x_c, ctx->norm_final, nullptr, Mvi, d, m.rms_eps, h_verify, partials, pending, (int64_t)Mvi * d, ctx->dev_flags, ctx->bf16_ops, st);
     } else {
         ProfScope ps(ctx, SSD_PROF_OTHER);
-        launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, Mvi, d, m.rms_eps, h_verify, partials, pending, split_stride, ctx->dev_flags, st);
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, d_vrow, Mvi, d, m.rms_eps, h_verify, partials, pending, split_stride, ctx->dev_flags, ctx->bf16_ops, st);
     }
     HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
@@ -1029,45 +1034,45 @@ int ar_fallback(ssd_ctx* ctx, int Br, const int32_t* kv_start, const int32_t* ct
         launch_embed_rows(m.dtype, nullptr, ctx->embed, nullptr, tok_in, d_row_src, Br, d, m.vocab, x, ctx->dev_flags, st);
         int pending = 1;
         for (int l = 0; l < m.n_layers; ++l) {
-            launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st);
+            launch_rmsnorm(m.dtype, x, ctx->norm_attn[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, ctx->bf16_ops, st);
             pending = 1;
             if (m.dtype == SSD_BF16) {
                 // few rows, head_dim 128: the QKV projection stays K-split and the decode attention finishes it
                 const int qsplits = (Br <= 32 && m.head_dim == 128)
-                    ? launch_gemm_qkv_partial((const uint16_t*)a, ctx->s_qkv[l], qkv_part, Br, d, dq + 2 * dkv, ctx->ds_qkv[l], st) : 0;
+                    ? launch_gemm_qkv_partial((const uint16_t*)a, ctx->s_qkv[l], qkv_part, Br, d, dq + 2 * dkv, ctx->ds_qkv[l], ctx->bf16_ops, st) : 0;
                 if (qsplits) {
                     launch_decode_attn_fused(qkv_part, qsplits, ctx->rope_tab, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br,
-                                             m.n_q_heads, m.n_kv_heads, att, ctx->dev_flags, st);
+                                             m.n_q_heads, m.n_kv_heads, att, ctx->dev_flags, ctx->bf16_ops, st);
                 } else {
                     launch_gemm_qkv_rope((const uint16_t*)a, (const uint16_t*)ctx->wqkv[l], ctx->s_qkv[l], (uint16_t*)qkv, d_pos, ctx->rope_tab, Br, d, dq, dkv, ctx->ds_qkv[l],
-                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), nullptr, ctx->dev_flags, st);
-                    launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                                         d_slot, (uint16_t*)kv_k(ctx, l), (uint16_t*)kv_v(ctx, l), nullptr, ctx->dev_flags, ctx->bf16_ops, st);
+                    launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, ctx->bf16_ops, st);
                 }
-                pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], st);
-                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, st);
+                pending = launch_gemm_residual((const uint16_t*)att, (const uint16_t*)ctx->wo[l], ctx->s_o[l], x, partials, Br, d, dq, ctx->ds_o[l], ctx->bf16_ops, st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, partials, pending, split_stride, ctx->dev_flags, ctx->bf16_ops, st);
                 pending = 1;
-                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, st);
-                pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], st);
+                launch_gemm_swiglu((const uint16_t*)a, (const uint16_t*)ctx->wgu[l], ctx->s_gu[l], (uint16_t*)h, Br, m.d_ff, d, ctx->ds_gu[l], ctx->dev_flags, ctx->bf16_ops, st);
+                pending = launch_gemm_residual((const uint16_t*)h, (const uint16_t*)ctx->w_down[l], ctx->s_down[l], x, partials, Br, d, m.d_ff, ctx->ds_down[l], ctx->bf16_ops, st);
             } else {
                 float* gu = reinterpret_cast<float*>(ws + p.gu);
                 launch_gemm_f32((const float*)a, (const float*)ctx->wqkv[l], (float*)qkv, Br, dq + 2 * dkv, d, F32_STORE, st);
                 launch_rope_f32((float*)qkv, d_pos, ctx->rope_tab, Br, m.n_q_heads + m.n_kv_heads, m.head_dim, dq + 2 * dkv, st);
                 launch_kv_store(m.dtype, qkv, d_slot, Br, dq, dkv, kv_k(ctx, l), kv_v(ctx, l), st);
-                launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, st);
+                launch_decode_attn(m.dtype, qkv, kv_k(ctx, l), kv_v(ctx, l), d_kvs, d_nctx, Br, m.n_q_heads, m.n_kv_heads, m.head_dim, att, ctx->bf16_ops, st);
                 launch_gemm_f32((const float*)att, (const float*)ctx->wo[l], x, Br, d, dq, F32_ADD, st);
-                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, st);
+                launch_rmsnorm(m.dtype, x, ctx->norm_mlp[l], nullptr, Br, d, m.rms_eps, a, nullptr, 1, 0, ctx->dev_flags, ctx->bf16_ops, st);
                 launch_gemm_f32((const float*)a, (const float*)ctx->wgu[l], gu, Br, 2 * m.d_ff, d, F32_STORE, st);
                 launch_swiglu_f32(gu, (float*)h, Br, m.d_ff, st);
                 launch_gemm_f32((const float*)h, (const float*)ctx->w_down[l], x, Br, d, m.d_ff, F32_ADD, st);
             }
         }
-        launch_rmsnorm(m.dtype, x, ctx->norm_final, nullptr, Br, d, m.rms_eps, hfin, partials, pending, split_stride, ctx->dev_flags, st);
+        launch_rmsnorm(m.dtype, x, ctx->norm_final, nullptr, Br, d, m.rms_eps, hfin, partials, pending, split_stride, ctx->dev_flags, ctx->bf16_ops, st);
         int32_t* tok_out = out_tokens + (size_t)t * Br;
         if (m.dtype == SSD_BF16) {
             float2* part_ms = reinterpret_cast<float2*>(ws + p.part_ms);
             float* tgt = reinterpret_cast<float*>(ws + p.tgt);
             int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
-            launch_lmhead_mfma((const uint16_t*)hfin, (const uint16_t*)ctx->lm_head, tok_in, Br, d, m.vocab, part_ms, tgt, part_arg, true, ctx->ds_lm, st);
+            launch_lmhead_mfma((const uint16_t*)hfin, (const uint16_t*)ctx->lm_head, tok_in, Br, d, m.vocab, part_ms, tgt, part_arg, true, ctx->ds_lm, ctx->bf16_ops, st);
             launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), Br, logp, tok_out, ctx->dev_flags, st);
         } else {
             launch_lmhead_f32((const float*)hfin, (const float*)ctx->lm_head, tok_in, Br, d, m.vocab, logp, tok_out, st);
@@ -1104,7 +1109,7 @@ int accept_prefix(ssd_ctx* ctx, const void* h_verify, const int32_t* draft_ids, 
         float* tgt = reinterpret_cast<float*>(ws + p.tgt);
         int2* part_arg = reinterpret_cast<int2*>(ws + p.part_arg);
         launch_lmhead_mfma((const uint16_t*)h_verify, (const uint16_t*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,
-                           part_ms, tgt, part_arg, greedy_tok != nullptr, ctx->ds_lm, st);
+                           part_ms, tgt, part_arg, greedy_tok != nullptr, ctx->ds_lm, ctx->bf16_ops, st);
         launch_lmhead_finalize(part_ms, tgt, part_arg, lmhead_col_groups(m.vocab), (int)Mv, draft_logp, greedy_tok, ctx->dev_flags, st);
     } else {
         launch_lmhead_f32((const float*)h_verify, (const float*)ctx->lm_head, draft_ids, (int)Mv, m.d_model, m.vocab,

@@ -42,21 +42,26 @@ void launch_kv_store(int dtype, const void* qkv, const int32_t* row_slot, int n_
 // output dimensions for P.V.  head_dim <= 128, multiple of 8.
 template <typename T> __device__ __forceinline__ float elem_to_f32(T v);
 template <> __device__ __forceinline__ float elem_to_f32<float>(float v) { return v; }
-template <> __device__ __forceinline__ float elem_to_f32<f16_t>(f16_t v) { return f16_to_f32(v); }
 template <typename T> __device__ __forceinline__ T f32_to_elem(float v);
 template <> __device__ __forceinline__ float f32_to_elem<float>(float v) { return v; }
-template <> __device__ __forceinline__ f16_t f32_to_elem<f16_t>(float v) { return f32_to_f16(v); }
 
 // eight consecutive elements as fp32
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
-__device__ __forceinline__ void load8(const f16_t* p, float (&v)[8]) {
-    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-    const h8 a = *reinterpret_cast<const h8*>(p);
+// eight 16-bit operand patterns (IEEE half or bfloat16) as fp32
+template <bool BF>
+__device__ __forceinline__ void unpack8(const uint4& w, float (&v)[8]) {
+    if constexpr (BF) {
+        v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+        v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+    } else {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        const h8 a = __builtin_bit_cast(h8, w);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+        for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+    }
 }
 
 template <typename T>
@@ -143,6 +148,16 @@ constexpr int DEC_WAVES = 4;
 // rotary pairs (i, i+64) sit 32 columns apart in 64-column groups, V columns are in natural order).
 // The kernel adds the splits, rotates q and the new k, appends the new k / v row to the cache (first query
 // head of each K/V group) and treats that row as the last key without reading it back.
+// a value as the cache / the next kernel will see it: rounded to the operand type, saturated for IEEE half
+template <bool BF> __device__ __forceinline__ float round_like_stored(float v, bool& bad) {
+    if constexpr (BF) return bf16_to_f32(f32_to_bf16(v));
+    else return f16_to_f32(f32_to_f16_sat(v, bad));
+}
+template <bool BF> __device__ __forceinline__ uint32_t pack2_sat(float lo, float hi, bool& bad) {
+    if constexpr (BF) return pack_bf16x2(lo, hi);
+    else return pack_f16x2_sat(lo, hi, bad);
+}
+
 struct DecodeFused {
     const float* part; int n_splits; int64_t split_stride;    // split_stride = rows * (d_q + 2 d_kv)
     const float2* rope_tab;                                   // [position][64] (cos, sin)
@@ -192,12 +207,11 @@ __device__ __forceinline__ void rotated_chunk(const DecodeFused& f, int64_t row_
     for (int e = 0; e < 8; ++e) v[e] = dc < 8 ? lo[e] * cs[e].x - hi[e] * cs[e].y : hi[e] * cs[e].x + lo[e] * cs[e].y;
 }
 
-template <bool FUSED>
+template <bool FUSED, bool BF>
 __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const f16_t* __restrict__ qkv, const f16_t* __restrict__ kc,
                                                                const f16_t* __restrict__ vc, const int32_t* __restrict__ kv_start,
                                                                const int32_t* __restrict__ n_ctx, int n_q_heads, int n_kv_heads,
                                                                f16_t* __restrict__ out, DecodeFused fu) {
-    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
     constexpr int HD = 128;
     __shared__ float merge_o[DEC_WAVES][16][8];
     __shared__ float merge_ml[DEC_WAVES][2];
@@ -241,23 +255,24 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
             rope_entries(fu, dc, p, cs);
             rotated_chunk(fu, row_off, h * HD, dc, cs, qf);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) qf[e] = f16_to_f32(f32_to_f16_sat(qf[e], bad)) * sc;      // q is rounded (and saturated) like a stored row
+            for (int e = 0; e < 8; ++e) qf[e] = round_like_stored<BF>(qf[e], bad) * sc;      // q is rounded (and saturated) like a stored row
             if (wave == 0) {
                 float kn[8], vn[8];
                 rotated_chunk(fu, row_off, d_q + kvh * HD, dc, cs, kn);
                 sum_splits8(fu, row_off, d_q + d_kv + kvh * HD + dc * 8, vn);
                 // the cache holds half precision: the new row takes part in this step with the values later steps read
                 uint4 kw;
-                kw.x = pack_f16x2_sat(kn[0], kn[1], bad); kw.y = pack_f16x2_sat(kn[2], kn[3], bad); kw.z = pack_f16x2_sat(kn[4], kn[5], bad); kw.w = pack_f16x2_sat(kn[6], kn[7], bad);
-                vw.x = pack_f16x2_sat(vn[0], vn[1], bad); vw.y = pack_f16x2_sat(vn[2], vn[3], bad); vw.z = pack_f16x2_sat(vn[4], vn[5], bad); vw.w = pack_f16x2_sat(vn[6], vn[7], bad);
+                kw.x = pack2_sat<BF>(kn[0], kn[1], bad); kw.y = pack2_sat<BF>(kn[2], kn[3], bad); kw.z = pack2_sat<BF>(kn[4], kn[5], bad); kw.w = pack2_sat<BF>(kn[6], kn[7], bad);
+                vw.x = pack2_sat<BF>(vn[0], vn[1], bad); vw.y = pack2_sat<BF>(vn[2], vn[3], bad); vw.z = pack2_sat<BF>(vn[4], vn[5], bad); vw.w = pack2_sat<BF>(vn[6], vn[7], bad);
                 if (h % (n_q_heads / n_kv_heads) == 0) {
                     const int64_t so = ((int64_t)kv_start[b] + n) * d_kv + kvh * HD + dc * 8;
                     *reinterpret_cast<uint4*>(fu.kc_w + so) = kw;
                     *reinterpret_cast<uint4*>(fu.vc_w + so) = vw;
                 }
-                const h8 kh = __builtin_bit_cast(h8, kw);
+                float kh[8];
+                unpack8<BF>(kw, kh);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s_new = fmaf(qf[e], (float)kh[e], s_new);
+                for (int e = 0; e < 8; ++e) s_new = fmaf(qf[e], kh[e], s_new);
             }
         }
         if (bad) raise_flag(fu.flags, SSD_FLAG_ACT_OVERFLOW);
@@ -268,13 +283,11 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         if (wave == 0) {                                     // the new row is wavefront 0's first key
             m = s_new; l = 1.f;
             if (kg == 0) {
-                const h8 vh = __builtin_bit_cast(h8, vw);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = (float)vh[e];
+                unpack8<BF>(vw, o);
             }
         }
     } else {
-        load8(qkv + (int64_t)b * (d_q + 2 * d_kv) + h * HD + dc * 8, qf);
+        unpack8<BF>(*reinterpret_cast<const uint4*>(qkv + (int64_t)b * (d_q + 2 * d_kv) + h * HD + dc * 8), qf);
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[e] *= sc;
     }
@@ -283,10 +296,11 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         float cm = -INFINITY;
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
-            const h8 kk = __builtin_bit_cast(h8, kr[it]);
+            float kk[8];
+            unpack8<BF>(kr[it], kk);
             float acc = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc = fmaf(qf[e], (float)kk[e], acc);
+            for (int e = 0; e < 8; ++e) acc = fmaf(qf[e], kk[e], acc);
             acc = group_allreduce<16>(acc, OpSum());
             s[it] = (k0 + it * 4 + kg < n) ? acc : -INFINITY;
             cm = fmaxf(cm, s[it]);
@@ -302,9 +316,10 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         for (int it = 0; it < 16; ++it) {
             const float p = __builtin_amdgcn_exp2f(s[it] - m_new);
             ps += p;
-            const h8 vv = __builtin_bit_cast(h8, vr[it]);
+            float vv[8];
+            unpack8<BF>(vr[it], vv);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = fmaf(p, (float)vv[e], o[e]);
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(p, vv[e], o[e]);
         }
         ps += __shfl_xor(ps, 16);
         ps += __shfl_xor(ps, 32);
@@ -341,35 +356,41 @@ __global__ void __launch_bounds__(64 * DEC_WAVES) decode_attn_hd128_kernel(const
         }
         const float inv = 1.0f / l;
         uint4 w;
-        w.x = pack_f16x2(o[0] * inv, o[1] * inv); w.y = pack_f16x2(o[2] * inv, o[3] * inv);
-        w.z = pack_f16x2(o[4] * inv, o[5] * inv); w.w = pack_f16x2(o[6] * inv, o[7] * inv);
+        w.x = op_pack2<BF>(o[0] * inv, o[1] * inv); w.y = op_pack2<BF>(o[2] * inv, o[3] * inv);
+        w.z = op_pack2<BF>(o[4] * inv, o[5] * inv); w.w = op_pack2<BF>(o[6] * inv, o[7] * inv);
         *reinterpret_cast<uint4*>(out + (int64_t)b * d_q + h * HD + dc * 8) = w;
     }
 }
 
 void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
                         const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
-                        hipStream_t st) {
+                        bool bf16_ops, hipStream_t st) {
     if (Br <= 0) return;
-    if (dtype == SSD_BF16 && head_dim == 128)
-        hipLaunchKernelGGL(decode_attn_hd128_kernel<false>, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
-                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, DecodeFused{});
-    else if (dtype == SSD_BF16)
-        hipLaunchKernelGGL(decode_attn_kernel<f16_t>, dim3(Br, n_q_heads), dim3(64), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
-                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (f16_t*)out);
-    else
+    if (dtype == SSD_BF16) {                                 // 16-bit models always have head_dim 128
+        if (bf16_ops)
+            hipLaunchKernelGGL((decode_attn_hd128_kernel<false, true>), dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+                               (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, DecodeFused{});
+        else
+            hipLaunchKernelGGL((decode_attn_hd128_kernel<false, false>), dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, (const f16_t*)qkv, (const f16_t*)kc,
+                               (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, DecodeFused{});
+    } else {
         hipLaunchKernelGGL(decode_attn_kernel<float>, dim3(Br, n_q_heads), dim3(64), 0, st, (const float*)qkv, (const float*)kc,
                            (const float*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, head_dim, (float*)out);
+    }
 }
 
 void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
                               const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
-                              void* out, int32_t* flags, hipStream_t st) {
+                              void* out, int32_t* flags, bool bf16_ops, hipStream_t st) {
     if (Br <= 0) return;
     const int64_t stride = (int64_t)Br * (n_q_heads + 2 * n_kv_heads) * 128;
     DecodeFused fu{qkv_part, n_splits, stride, reinterpret_cast<const float2*>(rope_tab), (f16_t*)kc, (f16_t*)vc, flags};
-    hipLaunchKernelGGL(decode_attn_hd128_kernel<true>, dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, nullptr, (const f16_t*)kc,
-                       (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, fu);
+    if (bf16_ops)
+        hipLaunchKernelGGL((decode_attn_hd128_kernel<true, true>), dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, nullptr, (const f16_t*)kc,
+                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, fu);
+    else
+        hipLaunchKernelGGL((decode_attn_hd128_kernel<true, false>), dim3(Br, n_q_heads), dim3(64 * DEC_WAVES), 0, st, nullptr, (const f16_t*)kc,
+                           (const f16_t*)vc, kv_start, n_ctx, n_q_heads, n_kv_heads, (f16_t*)out, fu);
 }
 
 }  // namespace ssd

@@ -1,4 +1,5 @@
-// Causal self-attention over ragged (varlen) utterances, head_dim 128, grouped KV heads, f16 MFMA.
+// Causal self-attention over ragged (varlen) utterances, head_dim 128, grouped KV heads, 16-bit MFMA (IEEE half
+// or bfloat16 operands: template parameter BF).
 // This is the mechanism that lets Eq. 5 be evaluated for all draft tokens in one forward (Sec. 2.2):
 // position p only attends to positions <= p of its own utterance.
 //
@@ -25,7 +26,7 @@ constexpr int ATT_V_STRIDE = ATT_KB + 8;      // Vt[dim][slot], elements
 // condition end up in scratch memory)
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-template <int RATIO>      // query heads per KV head
+template <int RATIO, bool BF>      // query heads per KV head; operand type (IEEE half / bfloat16)
 __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* __restrict__ qkv, f16_t* __restrict__ out,
                                                                 const AttnTile* __restrict__ tiles, int n_q_heads,
                                                                 int n_kv_heads) {
@@ -156,7 +157,7 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
             for (int p = 0; p < 4; ++p) kq[p] = k_frag(p);
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
-                s_acc[idx / 8] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kq[idx % 4], qf[idx % 8], s_acc[idx / 8], 0, 0, 0);
+                s_acc[idx / 8] = mfma_32x32x16<BF>(kq[idx % 4], qf[idx % 8], s_acc[idx / 8]);
                 if (idx + 4 < 16) kq[idx % 4] = k_frag(idx + 4);
             }
             // pin the order (the scheduler would sink every read to just before its MFMA)
@@ -207,7 +208,7 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
                         const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[c][8 * s + 2 * e], sc, -ms));
                         const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[c][8 * s + 2 * e + 1], sc, -ms));
                         rs += p0 + p1;
-                        w[e] = pack_f16x2(p0, p1);
+                        w[e] = op_pack2<BF>(p0, p1);
                     }
                     pf[c * 2 + s] = as_f16x8(make_uint4(w[0], w[1], w[2], w[3]));
                 }
@@ -221,7 +222,7 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
             // ---- O^T += V^T . P^T
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
-                o_acc[idx / 4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vq[idx % 4], pf[idx % 4], o_acc[idx / 4], 0, 0, 0);
+                o_acc[idx / 4] = mfma_32x32x16<BF>(vq[idx % 4], pf[idx % 4], o_acc[idx / 4]);
                 if (idx + 4 < 16) vq[idx % 4] = v_frag(idx + 4);
             }
 #pragma unroll
@@ -241,8 +242,8 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
             for (int g = 0; g < 4; ++g) {
                 const int dim = db * 32 + 8 * g + 4 * hgrp;
                 uint2 w;
-                w.x = pack_f16x2(o_acc[db][4 * g] * inv, o_acc[db][4 * g + 1] * inv);
-                w.y = pack_f16x2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
+                w.x = op_pack2<BF>(o_acc[db][4 * g] * inv, o_acc[db][4 * g + 1] * inv);
+                w.y = op_pack2<BF>(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
                 *reinterpret_cast<uint2*>(wtile + lcol * ATT_K_STRIDE + dim) = w;
             }
         __builtin_amdgcn_wave_barrier();
@@ -256,15 +257,21 @@ __global__ void __launch_bounds__(128 * RATIO, 2) attn_mfma_kernel(const f16_t* 
     }
 }
 
-void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
-                      int n_kv_heads, hipStream_t st) {
-    if (n_tiles <= 0) return;
+template <bool BF>
+static void attn_impl(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads, int n_kv_heads,
+                      hipStream_t st) {
     const int ratio = n_q_heads / n_kv_heads;
     const dim3 grid(n_tiles * n_kv_heads);
-    if (ratio == 1) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(128), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
-    else if (ratio == 2) hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
-    else if (ratio == 3) hipLaunchKernelGGL(attn_mfma_kernel<3>, grid, dim3(384), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
-    else hipLaunchKernelGGL(attn_mfma_kernel<4>, grid, dim3(512), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    if (ratio == 1) hipLaunchKernelGGL((attn_mfma_kernel<1, BF>), grid, dim3(128), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else if (ratio == 2) hipLaunchKernelGGL((attn_mfma_kernel<2, BF>), grid, dim3(256), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else if (ratio == 3) hipLaunchKernelGGL((attn_mfma_kernel<3, BF>), grid, dim3(384), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+    else hipLaunchKernelGGL((attn_mfma_kernel<4, BF>), grid, dim3(512), 0, st, qkv, out, tiles, n_q_heads, n_kv_heads);
+}
+void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
+                      int n_kv_heads, bool bf16_ops, hipStream_t st) {
+    if (n_tiles <= 0) return;
+    if (bf16_ops) attn_impl<true>(qkv, out, tiles, n_tiles, n_q_heads, n_kv_heads, st);
+    else attn_impl<false>(qkv, out, tiles, n_tiles, n_q_heads, n_kv_heads, st);
 }
 
 }  // namespace ssd

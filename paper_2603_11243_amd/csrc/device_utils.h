@@ -60,6 +60,26 @@ template <bool CLAMP>
 __device__ __forceinline__ uint32_t f16x2_store(float lo, float hi, float& peak) {
     return (uint32_t)f16_store<CLAMP>(lo, peak) | ((uint32_t)f16_store<CLAMP>(hi, peak) << 16);
 }
+// The 16-bit matrix-core operand type is a property of the context: IEEE half (BF = false: 11 significant bits,
+// range 65504, stores saturate as above) or bfloat16 (BF = true: 8 significant bits, the range of fp32, nothing
+// to saturate).  Kernels carry it as a template parameter; both are raw 16-bit patterns in memory.
+template <bool BF> struct Op16;
+template <> struct Op16<false> {
+    static __device__ __forceinline__ uint16_t cvt(float v) { return f32_to_f16(v); }
+    static __device__ __forceinline__ float to_f32(uint16_t b) { return f16_to_f32(b); }
+    template <bool CLAMP> static __device__ __forceinline__ uint16_t store(float v, float& peak) { return f16_store<CLAMP>(v, peak); }
+};
+template <> struct Op16<true> {
+    static __device__ __forceinline__ uint16_t cvt(float v) { return f32_to_bf16(v); }
+    static __device__ __forceinline__ float to_f32(uint16_t b) { return bf16_to_f32(b); }
+    template <bool CLAMP> static __device__ __forceinline__ uint16_t store(float v, float&) { return f32_to_bf16(v); }
+};
+template <bool BF> __device__ __forceinline__ uint32_t op_pack2(float lo, float hi) {
+    return (uint32_t)Op16<BF>::cvt(lo) | ((uint32_t)Op16<BF>::cvt(hi) << 16);
+}
+template <bool BF, bool CLAMP> __device__ __forceinline__ uint32_t op_store2(float lo, float hi, float& peak) {
+    return (uint32_t)Op16<BF>::template store<CLAMP>(lo, peak) | ((uint32_t)Op16<BF>::template store<CLAMP>(hi, peak) << 16);
+}
 // flag bits are those of enum ssd_device_flag (a vector atomic: several kernels may raise different bits)
 __device__ __forceinline__ void raise_flag(int32_t* flags, int bit) {
     if (flags) atomicOr(flags, bit);

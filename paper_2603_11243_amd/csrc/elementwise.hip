@@ -81,7 +81,7 @@ void launch_gather_ids(const int32_t* src, const int32_t* idx, int n, const int3
 // RMSNorm: out[r] = x[row] * gain / sqrt(mean(x[row]^2) + eps), row = row_idx ? row_idx[r] : r.
 // One wavefront per row; statistics in fp32.  d must be a multiple of 4.
 // T = bf16 gain with f16 output (MFMA operand type), or fp32 gain with fp32 output.
-template <typename T, int NV>
+template <typename T, int NV, bool BF>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                       const int32_t* __restrict__ row_idx, int n_rows, int d,
                                                       float eps, T* __restrict__ out, const float* __restrict__ partials,
@@ -145,8 +145,8 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
             if constexpr (sizeof(T) == 2) {
                 const uint2 g = g16[j];
                 uint2 o;
-                o.x = f16x2_store<CLAMP>(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x), peak);
-                o.y = f16x2_store<CLAMP>(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y), peak);
+                o.x = op_store2<BF, CLAMP>(v[j].x * inv * bf16_lo(g.x), v[j].y * inv * bf16_hi(g.x), peak);
+                o.y = op_store2<BF, CLAMP>(v[j].z * inv * bf16_lo(g.y), v[j].w * inv * bf16_hi(g.y), peak);
                 reinterpret_cast<uint2*>(dst)[i] = o;
             } else {
                 const float4 g = reinterpret_cast<const float4*>(gain)[i];
@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
 // Same operation with one workgroup per row, for launches with few rows (there a wavefront per row
 // leaves most of the chip idle and serialises the split sums): every thread owns d/1024 float4s
 // and all its split loads are issued together.
-template <typename T, int MAXV>
+template <typename T, int MAXV, bool BF>
 __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x, const T* __restrict__ gain,
                                                           const int32_t* __restrict__ row_idx, int d, float eps,
                                                           T* __restrict__ out, const float* __restrict__ partials,
@@ -219,8 +219,8 @@ __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x,
             if constexpr (sizeof(T) == 2) {
                 const uint2 g = g16[k];
                 uint2 o;
-                o.x = f16x2_store<CLAMP>(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x), peak);
-                o.y = f16x2_store<CLAMP>(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y), peak);
+                o.x = op_store2<BF, CLAMP>(v[k].x * inv * bf16_lo(g.x), v[k].y * inv * bf16_hi(g.x), peak);
+                o.y = op_store2<BF, CLAMP>(v[k].z * inv * bf16_lo(g.y), v[k].w * inv * bf16_hi(g.y), peak);
                 reinterpret_cast<uint2*>(dst)[i] = o;
             } else {
                 const float4 g = reinterpret_cast<const float4*>(gain)[i];
@@ -236,25 +236,29 @@ __global__ void __launch_bounds__(256) rmsnorm_row_kernel(float* __restrict__ x,
 }
 
 void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d, float eps,
-                    void* out, const float* partials, int n_splits, int64_t split_stride, int32_t* flags, hipStream_t st) {
+                    void* out, const float* partials, int n_splits, int64_t split_stride, int32_t* flags, bool bf16_ops,
+                    hipStream_t st) {
     if (n_rows <= 0) return;
     if (n_rows <= 512 && d <= 4096 && n_splits <= SKINNY_MAX_SPLITS) {
-        if (dtype == SSD_BF16)
-            hipLaunchKernelGGL((rmsnorm_row_kernel<bf16_t, 4>), dim3(n_rows), dim3(256), 0, st, x, (const bf16_t*)gain, row_idx, d, eps, (bf16_t*)out, partials, n_splits, split_stride, flags);
-        else
-            hipLaunchKernelGGL((rmsnorm_row_kernel<float, 4>), dim3(n_rows), dim3(256), 0, st, x, (const float*)gain, row_idx, d, eps, (float*)out, partials, n_splits, split_stride, flags);
+#define SSD_RMSNORM_ROW(T, BF) \
+        hipLaunchKernelGGL((rmsnorm_row_kernel<T, 4, BF>), dim3(n_rows), dim3(256), 0, st, x, (const T*)gain, row_idx, d, eps, (T*)out, partials, n_splits, split_stride, flags)
+        if (dtype == SSD_BF16) { if (bf16_ops) SSD_RMSNORM_ROW(bf16_t, true); else SSD_RMSNORM_ROW(bf16_t, false); }
+        else SSD_RMSNORM_ROW(float, false);
+#undef SSD_RMSNORM_ROW
         return;
     }
     const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
-#define SSD_RMSNORM(T, NV) \
-    hipLaunchKernelGGL((rmsnorm_kernel<T, NV>), grid, block, 0, st, x, (const T*)gain, row_idx, n_rows, d, eps, (T*)out, partials, n_splits, split_stride, flags)
+#define SSD_RMSNORM(T, NV, BF) \
+    hipLaunchKernelGGL((rmsnorm_kernel<T, NV, BF>), grid, block, 0, st, x, (const T*)gain, row_idx, n_rows, d, eps, (T*)out, partials, n_splits, split_stride, flags)
+#define SSD_RMSNORM_OP(NV) do { if (bf16_ops) SSD_RMSNORM(bf16_t, NV, true); else SSD_RMSNORM(bf16_t, NV, false); } while (0)
     if (dtype == SSD_BF16) {
-        if (d <= 2048) SSD_RMSNORM(bf16_t, 8);
-        else if (d <= 4096) SSD_RMSNORM(bf16_t, 16);
-        else SSD_RMSNORM(bf16_t, 32);          // d_model <= 8192 is checked at context creation
+        if (d <= 2048) SSD_RMSNORM_OP(8);
+        else if (d <= 4096) SSD_RMSNORM_OP(16);
+        else SSD_RMSNORM_OP(32);               // d_model <= 8192 is checked at context creation
     } else {
-        SSD_RMSNORM(float, 4);                 // fp32 models have d_model <= 1024
+        SSD_RMSNORM(float, 4, false);          // fp32 models have d_model <= 1024
     }
+#undef SSD_RMSNORM_OP
 #undef SSD_RMSNORM
 }
 
@@ -262,8 +266,9 @@ void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_id
 // Weight re-layout (once, at context creation).
 //
 // bf16 weights become f16 MFMA operands: w * scale with scale a power of two chosen from the
-// tensor's largest magnitude, so every bf16 value (8 significant bits) is represented exactly.
-// fp32 weights are copied unchanged (scale 1).
+// tensor's largest magnitude, so that bf16 values (8 significant bits) within 31 binades of it are
+// represented exactly.  A scale of 0 keeps the bf16 bit pattern (contexts with bfloat16 operands).
+// fp32 weights are copied unchanged.
 template <typename T> struct Packed;
 // `lost` counts the values whose half representation differs from w * scale: a bf16 value keeps all its 8
 // significant bits only within 31 binades below the largest magnitude of its tensor (which lands just below
@@ -272,6 +277,7 @@ template <> struct Packed<float> { typedef float type; static __device__ __force
 template <> struct Packed<bf16_t> {
     typedef f16_t type;
     static __device__ __forceinline__ f16_t cvt(bf16_t v, float scale, unsigned& lost) {
+        if (scale <= 0.f) return v;                          // bfloat16 operands: the stored pattern is the operand
         const float t = bf16_to_f32(v) * scale;
         const f16_t h = f32_to_f16(t);
         lost += (f16_to_f32(h) != t) ? 1u : 0u;

@@ -50,6 +50,20 @@ constexpr size_t gemm_lds_bytes() { return (size_t)NSTAGE * (BM + BN) * GEMM_ROW
 
 __device__ __forceinline__ f16x8_t as_f16x8(const uint4& v) { return __builtin_bit_cast(f16x8_t, v); }
 
+// The two matrix instructions of the 16-bit path for either operand type (f16x8_t is the 16-byte container of
+// eight operand bit patterns in both cases); same shapes, same rate.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <bool BF>
+__device__ __forceinline__ f32x16_t mfma_32x32x16(const f16x8_t& a, const f16x8_t& b, const f32x16_t& c) {
+    if constexpr (BF) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+template <bool BF>
+__device__ __forceinline__ f32x4_t mfma_16x16x32(const f16x8_t& a, const f16x8_t& b, const f32x4_t& c) {
+    if constexpr (BF) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
 // Row / column of accumulator register r of block (i, j) for this lane, relative to the wave tile.
 __device__ __forceinline__ int acc_row(int i, int r, int lane) { return i * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4); }
 __device__ __forceinline__ int acc_col(int j, int lane) { return j * 32 + (lane % 32); }
@@ -136,11 +150,7 @@ struct GemmTile {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    if constexpr (BF16)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[i]),
-                                                                            __builtin_bit_cast(bf16x8_t, b[j]), acc[i][j], 0, 0, 0);
-                    else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = mfma_32x32x16<BF16>(a[i], b[j], acc[i][j]);
         };
 
         // Software pipeline over n = kt1 - kt0 slices; slice i lives in stage i % NSTAGE.

@@ -22,7 +22,6 @@
 
 namespace ssd {
 
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 // Row / column of accumulator register r of 16x16 block (i, j) for this lane, relative to the wave tile.
 struct Layout16 {
@@ -38,7 +37,7 @@ struct Layout32 {
     static __device__ __forceinline__ int col(int j, int lane) { return acc_col(j, lane); }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool BF16 = false>
 struct GemmTile16 {
     static constexpr int NSTAGE = 2;
     static constexpr int WAVES = WAVES_M * WAVES_N;
@@ -110,7 +109,7 @@ struct GemmTile16 {
             for (int i = 0; i < TH; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[half * TH + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], b[j], acc[half * TH + i][j], 0, 0, 0);
+                    acc[half * TH + i][j] = mfma_16x16x32<BF16>(a[i], b[j], acc[half * TH + i][j]);
         };
         // scheduling patterns: one MFMA, one LDS read, for the first n_reads MFMAs of a phase
         constexpr int PH = TH * TN;                          // MFMAs per phase

@@ -1,4 +1,5 @@
-// The three projection GEMMs of a decoder layer (Eq. 4's network), f16 MFMA with fused epilogues:
+// The three projection GEMMs of a decoder layer (Eq. 4's network), 16-bit MFMA (IEEE half or bfloat16 operands,
+// a template parameter of every kernel here) with fused epilogues:
 //   QKV      : a[M,d] x Wqkv^T  -> rotary embedding on q,k in fp32 -> f16 qkv[M, d_q + 2 d_kv]
 //   residual : o[M,K] x W^T     -> x[M,N] += acc                (attention output and MLP down projection)
 //   SwiGLU   : b[M,d] x Wgu^T   -> h[M,d_ff] = silu(gate) * up  (f16)
@@ -45,8 +46,9 @@ constexpr int residual_batch(int tm, int g0) {             // largest divisor of
         if (tm % c == 0 && c <= g0) g = c;
     return g;
 }
+template <bool BF_>
 struct EpiResidual {
-    static constexpr bool WANTS_SPLIT = false;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_;
     float* x; int ldx; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -79,8 +81,9 @@ struct EpiResidual {
     }
 };
 
+template <bool BF_>
 struct EpiQkvRope {
-    static constexpr bool WANTS_SPLIT = false;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_;
     f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
@@ -145,7 +148,7 @@ struct EpiQkvRope {
                             const float a = acc[i0 + g][j][r] * descale, b = acc[i0 + g][j + L::PAIR][r] * descale;
                             const float2 c = cs[g][jj][r];
                             f16_t* o = qkv + (int64_t)row * ldq;
-                            const f16_t v0 = f16_store<CLAMP>(a * c.x - b * c.y, peak), v1 = f16_store<CLAMP>(b * c.x + a * c.y, peak);
+                            const f16_t v0 = Op16<BF>::template store<CLAMP>(a * c.x - b * c.y, peak), v1 = Op16<BF>::template store<CLAMP>(b * c.x + a * c.y, peak);
                             o[c0] = v0;
                             o[c1] = v1;
                             if (slot[g][r] >= 0 && c0 >= d_q) {           // a group of 64 lies inside q, k or v
@@ -167,8 +170,9 @@ struct EpiQkvRope {
     }
 };
 
+template <bool BF_>
 struct EpiSwiglu {
-    static constexpr bool WANTS_SPLIT = false;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_;
     f16_t* h; int d_ff; float descale; int32_t* flags;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -190,7 +194,7 @@ struct EpiSwiglu {
                         const float g = acc[i][j][r] * descale, u = acc[i][j + L::PAIR][r] * descale;
                         // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division: the epilogue is
                         // 48 outputs per lane and the division was half of its instructions
-                        h[(int64_t)row * d_ff + f] = f16_store<CLAMP>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)), peak);
+                        h[(int64_t)row * d_ff + f] = Op16<BF>::template store<CLAMP>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)), peak);
                     }
             }
         };
@@ -204,8 +208,9 @@ struct EpiSwiglu {
 
 // Stores the scaled accumulator as an fp32 partial sum of one K split: part[split][row][col].
 // Whoever consumes it (the RMSNorm that follows) adds the splits in a fixed order.
+template <bool BF_>
 struct EpiPartial {
-    static constexpr bool WANTS_SPLIT = true;
+    static constexpr bool WANTS_SPLIT = true, BF = BF_;
     float* part; int ld; int64_t split_stride; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
@@ -226,7 +231,7 @@ struct EpiPartial {
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, int splits, Epi epi) {
-    using Tile = GemmTile<BM, BN, WAVES_M, WAVES_N, NSTAGE>;
+    using Tile = GemmTile<BM, BN, WAVES_M, WAVES_N, NSTAGE, Epi::BF>;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     const int split = blockIdx.x % splits;
@@ -268,7 +273,7 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
 template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma16_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
-    using Tile = GemmTile16<BM, BN, WAVES_M, WAVES_N>;
+    using Tile = GemmTile16<BM, BN, WAVES_M, WAVES_N, Epi::BF>;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     int tm, tn;
@@ -305,7 +310,7 @@ static void launch_gemm16(const f16_t* A, const f16_t* W, int M, int N, int K, c
 constexpr int STREAM_MAX_ROWS = 32;
 template <int NW, int DEPTH, class Epi>
 static void launch_stream_cfg(const f16_t* A, const void* Ws, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
-    auto kern = gemm_stream_kernel<NW, DEPTH, Epi>;
+    auto kern = gemm_stream_kernel<NW, DEPTH, Epi::BF, Epi>;
     constexpr size_t lds = gemm_stream_lds_bytes<NW, DEPTH>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -376,21 +381,31 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
                           const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, int32_t* flags,
-                          hipStream_t st) {
+                          bool bf16_ops, hipStream_t st) {
     const int N = d_q + 2 * d_kv;
-    EpiQkvRope epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q,
-                   reinterpret_cast<const float2*>(rope_rows), flags};
-    launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
+    if (bf16_ops) {
+        EpiQkvRope<true> epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q,
+                             reinterpret_cast<const float2*>(rope_rows), flags};
+        launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
+    } else {
+        EpiQkvRope<false> epi{qkv, N, d_q + d_kv, descale, pos, reinterpret_cast<const float2*>(rope_tab), row_slot, kc, vc, d_q,
+                              reinterpret_cast<const float2*>(rope_rows), flags};
+        launch_by_shape(A, Wqkv_packed, W_stream, M, N, d_model, epi, st);
+    }
 }
 
 int launch_gemm_qkv_partial(const uint16_t* A, const void* W_stream, float* part, int M, int d_model, int N, float descale,
-                            hipStream_t st) {
+                            bool bf16_ops, hipStream_t st) {
     if (!W_stream || M > STREAM_MAX_ROWS) return 0;
     int splits = 0;
     for (int s = SKINNY_MAX_SPLITS; s >= 2 && !splits; --s)                 // about one workgroup per CU
         if (stream_shape_ok(M, N, d_model, s) && (N / 64) * s <= 320) splits = s;
     if (!splits) return 0;
-    EpiPartial epi{part, N, (int64_t)M * N, descale};
+    if (bf16_ops) {
+        EpiPartial<true> epi{part, N, (int64_t)M * N, descale};
+        return try_launch_stream(A, W_stream, M, N, d_model, splits, epi, st) ? splits : 0;
+    }
+    EpiPartial<false> epi{part, N, (int64_t)M * N, descale};
     return try_launch_stream(A, W_stream, M, N, d_model, splits, epi, st) ? splits : 0;
 }
 
@@ -410,23 +425,34 @@ int gemm_residual_splits(int M, int N, int K, bool have_stream) {
 // of them for weight streaming; the splits land in `partials` ([splits][M][N] fp32) and the caller
 // hands them to the next RMSNorm, which adds them to x in a fixed order.  Returns the split count
 // (1: x has been updated in place).
-int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
-                         float descale, hipStream_t st) {
+template <bool BF>
+static int gemm_residual_impl(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
+                              float descale, hipStream_t st) {
     const int splits = gemm_residual_splits(M, N, K, W_stream != nullptr);
     if (splits > 1) {
-        EpiPartial epi{partials, N, (int64_t)M * N, descale};
+        EpiPartial<BF> epi{partials, N, (int64_t)M * N, descale};
         launch_skinny(A, W, W_stream, M, N, K, splits, epi, st);
         return splits;
     }
-    EpiResidual epi{x, N, descale};
+    EpiResidual<BF> epi{x, N, descale};
     launch_by_shape(A, W, W_stream, M, N, K, epi, st);
     return 1;
 }
+int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
+                         float descale, bool bf16_ops, hipStream_t st) {
+    return bf16_ops ? gemm_residual_impl<true>(A, W, W_stream, x, partials, M, N, K, descale, st)
+                    : gemm_residual_impl<false>(A, W, W_stream, x, partials, M, N, K, descale, st);
+}
 
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
-                        float descale, int32_t* flags, hipStream_t st) {
-    EpiSwiglu epi{h, d_ff, descale, flags};
-    launch_by_shape(A, Wgu_packed, W_stream, M, 2 * d_ff, K, epi, st);
+                        float descale, int32_t* flags, bool bf16_ops, hipStream_t st) {
+    if (bf16_ops) {
+        EpiSwiglu<true> epi{h, d_ff, descale, flags};
+        launch_by_shape(A, Wgu_packed, W_stream, M, 2 * d_ff, K, epi, st);
+    } else {
+        EpiSwiglu<false> epi{h, d_ff, descale, flags};
+        launch_by_shape(A, Wgu_packed, W_stream, M, 2 * d_ff, K, epi, st);
+    }
 }
 
 }  // namespace ssd

@@ -36,7 +36,7 @@ constexpr size_t gemm_stream_lds_bytes() {
     return (size_t)NW * (DEPTH * 4096 > 8192 ? DEPTH * 4096 : 8192);
 }
 
-template <int NW, int DEPTH, class Epi>
+template <int NW, int DEPTH, bool BF, class Epi>
 __global__ void __launch_bounds__(64 * NW)
 gemm_stream_kernel(const f16_t* __restrict__ A, const u32x4_t* __restrict__ Ws, int M, int N, int K, int splits, Epi epi) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -101,7 +101,7 @@ gemm_stream_kernel(const f16_t* __restrict__ A, const u32x4_t* __restrict__ Ws, 
                 const f16x8_t a = as_f16x8(*reinterpret_cast<const uint4*>(my_lds + d * 4096 + a_rd[s]));
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, __builtin_bit_cast(f16x8_t, w[d][j][s]), acc[j], 0, 0, 0);
+                    acc[j] = mfma_32x32x16<BF>(a, __builtin_bit_cast(f16x8_t, w[d][j][s]), acc[j]);
             }
     }
 

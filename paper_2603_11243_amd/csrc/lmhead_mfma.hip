@@ -15,12 +15,12 @@ constexpr int LM_WTN = 64;          // columns per group: every tile variant bel
 
 int lmhead_col_groups(int vocab) { return vocab / LM_WTN; }
 
-template <int LM_BM, int LM_BN, int LM_WM, int LM_WN, int LM_NS, bool GREEDY>
+template <int LM_BM, int LM_BN, int LM_WM, int LM_WN, int LM_NS, bool GREEDY, bool BF>
 __global__ void __launch_bounds__(64 * LM_WM * LM_WN)
 lmhead_mfma_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,
                    int Mv, int d, int vocab, float2* __restrict__ part_ms, float* __restrict__ tgt_logit,
                    int2* __restrict__ part_arg, float descale) {
-    using Tile = GemmTile<LM_BM, LM_BN, LM_WM, LM_WN, LM_NS>;
+    using Tile = GemmTile<LM_BM, LM_BN, LM_WM, LM_WN, LM_NS, BF>;
     static_assert(Tile::WTN == LM_WTN, "column groups are 64 wide");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (Mv + LM_BM - 1) / LM_BM;
@@ -107,11 +107,12 @@ constexpr size_t lmhead16_lds_bytes() {
     return ring > stage ? ring : stage;
 }
 
+template <bool BF>
 __global__ void __launch_bounds__(512)
 lmhead_mfma16_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_lm, const int32_t* __restrict__ targets,
                      int Mv, int d, int vocab, float2* __restrict__ part_ms, float* __restrict__ tgt_logit,
                      int2* __restrict__ part_arg, float descale, int want_greedy) {
-    using Tile = GemmTile16<256, 256, 2, 4>;
+    using Tile = GemmTile16<256, 256, 2, 4, BF>;
     static_assert(Tile::WTN == LM_WTN && Tile::WTM == 128, "a wavefront owns 128 rows x one column group");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (Mv + 255) / 256;
@@ -175,14 +176,14 @@ lmhead_mfma16_kernel(const f16_t* __restrict__ hv, const f16_t* __restrict__ w_l
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
+template <int BM, int BN, int WM, int WN, int NS, bool BF>
 static void launch_lmhead_cfg(const f16_t* hv, const f16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                               float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
                               hipStream_t st) {
     constexpr size_t lds = gemm_lds_bytes<BM, BN, NS>();
     const int tiles = ((Mv + BM - 1) / BM) * (vocab / BN);
-    auto kern_greedy = lmhead_mfma_kernel<BM, BN, WM, WN, NS, true>;
-    auto kern_plain = lmhead_mfma_kernel<BM, BN, WM, WN, NS, false>;
+    auto kern_greedy = lmhead_mfma_kernel<BM, BN, WM, WN, NS, true, BF>;
+    auto kern_plain = lmhead_mfma_kernel<BM, BN, WM, WN, NS, false, BF>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern_greedy), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -197,24 +198,32 @@ static void launch_lmhead_cfg(const f16_t* hv, const f16_t* w_lm, const int32_t*
 
 // Tile by row count: up to 32 rows the whole job is streaming W_lm once (32 x 256 tile, four-stage
 // ring); up to 128 rows a 128 x 64 tile; otherwise the compute-bound 256 x 256 tile (lmhead_mfma16_kernel).
-void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+template <bool BF>
+static void lmhead_impl(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                         float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
                         hipStream_t st) {
-    if (Mv <= 0) return;
-    if (Mv <= 32) launch_lmhead_cfg<32, 256, 1, 4, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
-    else if (Mv <= 128) launch_lmhead_cfg<128, 64, 4, 1, 4>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    if (Mv <= 32) launch_lmhead_cfg<32, 256, 1, 4, 4, BF>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    else if (Mv <= 128) launch_lmhead_cfg<128, 64, 4, 1, 4, BF>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
     else {
         constexpr size_t lds = lmhead16_lds_bytes();
         static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+        auto kern = lmhead_mfma16_kernel<BF>;
         static bool attr_set = false;
         if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(lmhead_mfma16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             attr_set = true;
         }
         const int tiles = ((Mv + 255) / 256) * (vocab / 256);
-        hipLaunchKernelGGL(lmhead_mfma16_kernel, dim3(tiles), dim3(512), lds, st, (const f16_t*)hv, (const f16_t*)w_lm, targets,
+        hipLaunchKernelGGL(kern, dim3(tiles), dim3(512), lds, st, (const f16_t*)hv, (const f16_t*)w_lm, targets,
                            Mv, d, vocab, part_ms, tgt_logit, part_arg, descale, want_greedy ? 1 : 0);
     }
+}
+void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d, int vocab,
+                        float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy, float descale,
+                        bool bf16_ops, hipStream_t st) {
+    if (Mv <= 0) return;
+    if (bf16_ops) lmhead_impl<true>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
+    else lmhead_impl<false>(hv, w_lm, targets, Mv, d, vocab, part_ms, tgt_logit, part_arg, want_greedy, descale, st);
 }
 
 // One wavefront per row merges the per-group partials.

@@ -59,7 +59,7 @@ void launch_gather_ids(const int32_t* src, const int32_t* idx, int n, const int3
 // flags (may be NULL): SSD_FLAG_ACT_OVERFLOW is raised when a half-precision output had to be saturated
 void launch_rmsnorm(int dtype, float* x, const void* gain, const int32_t* row_idx, int n_rows, int d,
                     float eps, void* out, const float* partials, int n_splits, int64_t split_stride, int32_t* flags,
-                    hipStream_t st);
+                    bool bf16_ops, hipStream_t st);
 
 // ---- f32_path.hip (all-fp32 decoder for the tiny configuration)
 enum F32Epilogue { F32_STORE = 0, F32_ADD = 1 };
@@ -72,8 +72,9 @@ void launch_attn_f32(const float* qkv, float* out, const AttnTile* tiles, int n_
 void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* targets, int Mv, int d, int vocab,
                        float* logp, int32_t* greedy, hipStream_t st);
 
-// ---- gemm_mfma.hip (f16 MFMA GEMMs with fused epilogues), attn_mfma.hip, lmhead_mfma.hip.
-// Activations and converted weights are IEEE half bit patterns; `descale` undoes the weight scale.
+// ---- gemm_mfma.hip (16-bit MFMA GEMMs with fused epilogues), attn_mfma.hip, lmhead_mfma.hip.
+// Activations and converted weights are 16-bit operand patterns: IEEE half, or bfloat16 when bf16_ops is set (the
+// context's operand type); `descale` undoes the weight scale (1 for bfloat16 operands).
 // row_slot / kc / vc (all or none): rows with row_slot[row] >= 0 also store their rotated k part and their v
 // part into the K/V cache of this layer at that slot (what launch_kv_store does as a separate pass)
 // W_stream (may be NULL): the same weights in the stream layout of launch_stream_layout, read when at
@@ -82,31 +83,32 @@ void launch_lmhead_f32(const float* hv, const float* w_lm, const int32_t* target
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
                           const float* rope_tab, int M, int d_model, int d_q, int d_kv, float descale,
                           const int32_t* row_slot, uint16_t* kc, uint16_t* vc, const float* rope_rows, int32_t* flags,
-                          hipStream_t st);
+                          bool bf16_ops, hipStream_t st);
 constexpr int SKINNY_MAX_ROWS = 128;     // at most this many decoder rows: weight-streaming GEMM variants
 constexpr int SKINNY_MAX_SPLITS = 8;
 int gemm_residual_splits(int M, int N, int K, bool have_stream);
 // returns the number of K splits written to `partials` ([splits][M][N] fp32), or 1 if x was updated in place
 int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
-                         float descale, hipStream_t st);
+                         float descale, bool bf16_ops, hipStream_t st);
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
-                        float descale, int32_t* flags, hipStream_t st);
+                        float descale, int32_t* flags, bool bf16_ops, hipStream_t st);
 // second copy of an f16 weight matrix W[N,K] for the few-row kernel (N % 64 == 0, K % 256 == 0)
 bool stream_layout_supported(int N, int K);
 void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_t st);
 void launch_attn_mfma(const uint16_t* qkv, uint16_t* out, const AttnTile* tiles, int n_tiles, int n_q_heads,
-                      int n_kv_heads, hipStream_t st);
+                      int n_kv_heads, bool bf16_ops, hipStream_t st);
 // partial log-sum-exp of the LM head over column groups; see lmhead_mfma.hip
 int lmhead_col_groups(int vocab);
 void launch_lmhead_mfma(const uint16_t* hv, const uint16_t* w_lm, const int32_t* targets, int Mv, int d,
                         int vocab, float2* part_ms, float* tgt_logit, int2* part_arg, bool want_greedy,
-                        float descale, hipStream_t st);
+                        float descale, bool bf16_ops, hipStream_t st);
 // flags (may be NULL): SSD_FLAG_ACT_OVERFLOW is raised when a log-likelihood is not finite
 void launch_lmhead_finalize(const float2* part_ms, const float* tgt_logit, const int2* part_arg, int n_groups,
                             int Mv, float* logp, int32_t* greedy, int32_t* flags, hipStream_t st);
 
 // weight re-layout at context creation
-// (bf16 weights are converted to f16 times the power of two `scale`; fp32 weights are copied)
+// (bf16 weights are converted to f16 times the power of two `scale`, or kept as they are when scale is 0;
+// fp32 weights are copied)
 void launch_absmax(int dtype, const void* w, int64_t n, unsigned int* out_bits, hipStream_t st);
 // inexact (device counter, may be NULL) is increased by the number of values whose half representation is not exact
 void launch_convert_weight(int dtype, const void* w, void* out, int rows, int cols, float scale, unsigned long long* inexact,
@@ -122,7 +124,7 @@ void launch_kv_store(int dtype, const void* qkv, const int32_t* row_slot, int n_
                      void* vc, hipStream_t st);
 void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* vc, const int32_t* kv_start,
                         const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads, int head_dim, void* out,
-                        hipStream_t st);
+                        bool bf16_ops, hipStream_t st);
 
 // head_dim 128, half precision: decode attention that finishes the QKV projection itself.  qkv_part is
 // [n_splits][Br][d_q + 2 d_kv] fp32 partial sums in the packed column order of the fused QKV weight; the
@@ -131,11 +133,11 @@ void launch_decode_attn(int dtype, const void* qkv, const void* kc, const void* 
 // cached rows plus the new one.
 void launch_decode_attn_fused(const float* qkv_part, int n_splits, const float* rope_tab, void* kc, void* vc,
                               const int32_t* kv_start, const int32_t* n_ctx, int Br, int n_q_heads, int n_kv_heads,
-                              void* out, int32_t* flags, hipStream_t st);
+                              void* out, int32_t* flags, bool bf16_ops, hipStream_t st);
 // QKV projection left as K-split partial sums for launch_decode_attn_fused; returns the split count, or 0 if
 // the shape is not served (then nothing was launched)
 int launch_gemm_qkv_partial(const uint16_t* A, const void* W_stream, float* part, int M, int d_model, int N, float descale,
-                            hipStream_t st);
+                            bool bf16_ops, hipStream_t st);
 
 // threshold grids: outputs are [n_tau][B] / [n_tau][Bv]
 void launch_gate_grid(const float* max_entropy, int B, const float* taus_dev, int n_tau, uint8_t* gate_pass, hipStream_t st);

@@ -15,10 +15,10 @@ from workloads.configs import scaled_down
 pytestmark = pytest.mark.gpu
 
 
-def _run_chain(wl, w, vi, tau, n_steps):
+def _run_chain(wl, w, vi, tau, n_steps, operand="f16"):
     """verify (with K/V cache) -> accept (with greedy tokens) -> AR continuation of every utterance."""
     from paper_2603_11243_amd.binding import Context
-    ctx = Context(wl.model, w)
+    ctx = Context(wl.model, w, operand=operand)
     Bv = len(vi.cu_draft) - 1
     S, P, U = np.diff(vi.cu_speech), np.diff(vi.cu_prompt), np.diff(vi.cu_draft)
     n = S + P + U
@@ -44,10 +44,10 @@ def _run_chain(wl, w, vi, tau, n_steps):
     return acc_len, rej, first, toks, acc["draft_logp"].cpu().numpy()
 
 
-def _check_against_oracle(wl, w, vi, tau, n_steps, acc_len, rej, first, toks, logp_gpu, sample=None):
+def _check_against_oracle(wl, w, vi, tau, n_steps, acc_len, rej, first, toks, logp_gpu, sample=None, tol=None):
     """sample: positions in `rej` to check (default: every rejected utterance)."""
     from tests.test_gpu_verify import _subset
-    tol = TOL_LOGP[wl.model.dtype]
+    tol = TOL_LOGP[wl.model.dtype] if tol is None else tol
     ks = list(range(len(rej))) if sample is None else list(sample)
     sub = _subset(vi, [int(rej[k]) for k in ks])
     lp_sub = O.draft_logp(w, wl.model, sub.speech_emb, sub.cu_speech, sub.prompt_ids, sub.cu_prompt, sub.draft_ids, sub.cu_draft)
@@ -155,3 +155,21 @@ def test_ar_fallback_bf16_full_size_sampled_utterances(name):
     n_exact = _check_against_oracle(wl, w, vi, tau, n_steps, *res, sample=sample)
     print(f"{wl.name}: {n_exact} of {(n_steps + 1) * len(sample)} generated tokens identical to the oracle's")
     assert n_exact >= (n_steps + 1) * len(sample) // 2
+
+
+def test_ar_fallback_bfloat16_operands():
+    """The bfloat16 operand type through the whole chain (K/V cache rows, fused decode attention, few-row
+    projections): two 1B-width layers, tokens against the oracle's continuation with the wider tolerance of
+    that operand type for near-ties."""
+    wl = replace(scaled_down(WORKLOADS["cfg3_1b_ragged64"], n_layers=2, B=5), gate_rate=0.0)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, wl.seed, device="cuda")
+    tau = _tau_for(wl)
+    n_steps = 4
+    res = _run_chain(wl, w, vi, tau, n_steps, operand="bf16")
+    assert len(res[1]) >= 1
+    n_exact = _check_against_oracle(wl, w, vi, tau, n_steps, *res, tol=10 * TOL_LOGP["bf16"])
+    print(f"{wl.name}, bfloat16 operands: {n_exact} of {(n_steps + 1) * len(res[1])} generated tokens identical to the oracle's")
+    assert n_exact >= (n_steps + 1) * len(res[1]) // 2

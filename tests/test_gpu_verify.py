@@ -31,9 +31,9 @@ def _tau_for(wl, q=1.9):
     return float(np.exp(-np.log(wl.model.vocab) - s * s / 2 - q * s))
 
 
-def _run_gpu(wl, weights, vi, tau, want_greedy=True, reserve_tokens=None):
+def _run_gpu(wl, weights, vi, tau, want_greedy=True, reserve_tokens=None, operand="f16"):
     from paper_2603_11243_amd.binding import Context
-    ctx = Context(wl.model, weights)
+    ctx = Context(wl.model, weights, operand=operand)
     M = int(vi.cu_speech[-1] + vi.cu_prompt[-1] + vi.cu_draft[-1])
     ctx.reserve(max_tokens=reserve_tokens or M, max_verify_rows=int(vi.cu_draft[-1]), max_utts=len(vi.cu_draft) - 1)
     p_ids, d_ids = _dev(vi.prompt_ids), _dev(vi.draft_ids)
@@ -458,3 +458,27 @@ def test_sizes_beyond_32_bit_offsets_and_odd_head_dim_are_refused():
             ctx.ar_fallback([0], [5], _dev([1]), 2)
     finally:
         ctx.close()
+
+
+# ------------------------------------------------------------------ the two matrix-core operand types
+
+@pytest.mark.parametrize("name,layers,B", [("cfg2_1b_b1", 24, 1), ("cfg3_1b_ragged64", 4, 12)])
+def test_operand_types_against_oracle(name, layers, B):
+    """The same batch through both operand types of the 16-bit path: IEEE half (the default) and bfloat16 (what
+    the paper's stack runs in).  Both are compared with the oracle; half has to meet the stated 2e-2, bfloat16
+    (8 significant bits at every contraction input) is bounded by 10 times that and is expected to be worse."""
+    wl = replace(scaled_down(WORKLOADS[name], n_layers=layers, B=B), gate_rate=0.0)
+    cb = make_ctc_batch(wl)
+    fail, drafts = _gate_drafts(wl, cb)
+    vi = make_verify_inputs(wl, cb.seconds[fail], drafts, device="cuda")
+    w = make_model_weights(wl.model, wl.seed, device="cuda")
+    tau = _tau_for(wl)
+    worst, hidden = {}, {}
+    for operand, tol in (("f16", TOL_LOGP["bf16"]), ("bf16", 10 * TOL_LOGP["bf16"])):
+        res = _run_gpu(wl, w, vi, tau, operand=operand)
+        stats = {}
+        worst[operand] = _compare(wl, w, vi, res, tau, tol=tol, stats=stats)
+        hidden[operand] = stats["hidden_rel_err"]
+    print(f"{wl.name}: worst |dlogp| half {worst['f16']:.3e}, bfloat16 {worst['bf16']:.3e}; worst relative error of a "
+          f"hidden row half {hidden['f16']:.2e}, bfloat16 {hidden['bf16']:.2e}")
+    assert hidden["bf16"] > 2 * hidden["f16"]          # three mantissa bits fewer at every contraction input
