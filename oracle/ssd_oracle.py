@@ -118,6 +118,52 @@ def ctc_head_gate(enc_h, w_ctc, bias, cu_frames: Sequence[int], blank: int, tau_
     return ctc_gate(ctc_head_logits(enc_h, w_ctc, bias), cu_frames, blank, tau_ctc)
 
 
+# ------------------------------------------------------------------ projector windows
+
+def qformer_window_pool(enc_h, cu_frames: Sequence[int], q_proj, w_k, w_v, w_o, n_heads: int, window: int = 15):
+    """Windowed cross-attention of the query-transformer projector (Sec. 3.1: every window of 15 consecutive
+    frames is summarised by 3 trainable queries, a downsampling of the acoustic embeddings by 5).
+
+    enc_h  [sum_T, d_enc]  encoder states, utterance b owns rows cu_frames[b] .. cu_frames[b+1]-1
+    q_proj [n_q, d_h]      the trainable queries after their query projection (constants of the model)
+    w_k, w_v [d_h, d_enc]  key / value projections of the frames;  w_o [d_out, d_h]  output projection
+    For every utterance and every window w (frames 15 w .. 15 w + 14 of the utterance; the last window may be
+    shorter and attends over the frames it has), query j and head h (d_head = d_h / n_heads):
+        s_t = q_proj[j, head h] . (w_k enc_h[t])[head h] / sqrt(d_head),   p = softmax_t(s),
+        o[j, head h] = sum_t p_t (w_v enc_h[t])[head h],                   g[j] = w_o o[j].
+    Returns (g [sum_S, d_out], cu_speech) with S_b = n_q * ceil(T_b / window): the rows an utterance hands to
+    the LLM as speech embeddings, in window order, queries of a window next to each other.
+    Readings: the paper names the window, the query count and the rate only; the rest of a q-former layer
+    (self-attention among the queries, feed-forward block, normalisation, the second layer) is not described
+    and not part of this function; windows never cross an utterance boundary.
+    """
+    H = _f64(enc_h)
+    Q, Wk, Wv, Wo = _f64(q_proj), _f64(w_k), _f64(w_v), _f64(w_o)
+    n_q, d_h = Q.shape
+    if d_h % n_heads:
+        raise ValueError("d_h must be a multiple of n_heads")
+    dh = d_h // n_heads
+    rows, cu_speech = [], [0]
+    for b in range(len(cu_frames) - 1):
+        lo, hi = int(cu_frames[b]), int(cu_frames[b + 1])
+        if hi <= lo:
+            raise ValueError("an utterance needs at least one frame")
+        for w0 in range(lo, hi, window):
+            Hw = H[w0:min(w0 + window, hi)]
+            K, V = Hw @ Wk.T, Hw @ Wv.T
+            o = np.zeros((n_q, d_h))
+            for h in range(n_heads):
+                sl = slice(h * dh, (h + 1) * dh)
+                s = (Q[:, sl] @ K[:, sl].T) / math.sqrt(dh)          # [n_q, frames of the window]
+                s = s - s.max(axis=1, keepdims=True)
+                p = np.exp(s)
+                p = p / p.sum(axis=1, keepdims=True)
+                o[:, sl] = p @ V[:, sl]
+            rows.append(o @ Wo.T)
+        cu_speech.append(cu_speech[-1] + n_q * (-(-(hi - lo) // window)))
+    return np.concatenate(rows, axis=0), np.asarray(cu_speech, dtype=np.int32)
+
+
 # ------------------------------------------------------------------------ decoder
 
 def rmsnorm(x: np.ndarray, w: np.ndarray, eps: float) -> np.ndarray:
