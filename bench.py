@@ -31,7 +31,7 @@ PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense 16-bit matrix peak (bf16 and fp16)
 PEAK_HBM_GBS = 8000.0
 PEAK_F32_VALU_TFLOPS = 157.3   # the fp32 model runs on the vector ALUs
 
-LEGS = ["main", "cpu_baseline", "mfma_ceiling", "hbm_ceiling", "ar_fallback", "gate_saturation", "ctc_head",
+LEGS = ["main", "cpu_baseline", "mfma_ceiling", "hbm_ceiling", "ar_fallback", "gate_saturation", "ctc_head", "qformer",
         "other_configs", "two_phase", "library_gemm"]
 
 # HBM-side traffic of the dominant kernel (gate/up projection) per launch, from two rocprofv3 --pmc runs of
@@ -345,6 +345,39 @@ def ctc_head_leg(ctx, wl, device, d_enc=1024, V=348):
             "bytes_per_frame": {"fused": d_enc * 2 + 16 * ((V + 63) // 64) * 2 + 12, "unfused": d_enc * 2 + 2 * Vs * 2 + 12}}
 
 
+def qformer_leg(ctx, wl, device, d_enc=1024, d_h=1024, n_heads=16, window=15, n_q=3):
+    """The projector's windowed cross-attention (15 frames -> 3 queries) as the producer of the acoustic embeddings:
+    about 0.8 GB of encoder states in 400-frame utterances, HIP events through the library's profiler."""
+    if wl.model.dtype != "bf16":
+        return None
+    from workloads.synth import make_qformer_weights
+    T = 400
+    n_utts = int(0.8e9 / (d_enc * 2)) // T
+    n_rows = n_utts * T
+    cu = np.arange(n_utts + 1, dtype=np.int32) * T
+    gen = torch.Generator(device=device)
+    gen.manual_seed(6)
+    h = torch.randn(n_rows, d_enc, device=device, generator=gen).bfloat16()
+    qw = make_qformer_weights(wl.seed, n_q=n_q, d_h=d_h, d_enc=d_enc, d_out=wl.model.d_model, device=device)
+    ctx.set_qformer(qw["q_proj"], qw["w_k"], qw["w_v"], qw["w_o"], n_heads=n_heads, window=window)
+    ctx.reserve(max_frames=n_rows, max_utts=n_utts)
+    g, cu_s = ctx.qformer_pool(h, cu)
+    torch.cuda.synchronize()
+    ctx.profile_select("qformer_pool")
+    for _ in range(10):
+        ctx.qformer_pool(h, cu, out=g)
+    ms, n = ctx.profile_read()["qformer_pool"]
+    ctx.profile_select(-2)
+    ms /= n
+    S = int(cu_s[-1])
+    flops = 2.0 * n_rows * d_enc * (n_q * n_heads + d_h) + 2.0 * S * d_h * wl.model.d_model
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"frames": n_rows, "speech_rows": S, "d_enc": d_enc, "d_h": d_h, "d_out": wl.model.d_model, "ms_per_call": ms,
+            "frames_per_s": n_rows / (ms * 1e-3),
+            "roofline": {"bound": "mfma", "kernel": "two gemm_mfma16 launches (scores | values, output projection) + qformer_pool_kernel",
+                         "achieved": tf, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_TFLOPS, "flops_per_call": flops}}
+
+
 def ar_fallback_leg(ctx, wl, meta, tau, n_steps=16):
     """Eq. 6 after the timed path: verify with the K/V cache, accept with greedy tokens, then n_steps of
     greedy continuation for the utterances whose draft was not fully accepted.  A decode step streams
@@ -525,6 +558,10 @@ def main():
         ctx = Context(device=device)
         print(json.dumps({"ctc_head_gate": ctc_head_leg(ctx, wl, device)}))
         return
+    if only == "qformer":
+        ctx = Context(device=device)
+        print(json.dumps({"qformer_pool": qformer_leg(ctx, wl, device)}))
+        return
     if only == "other_configs":
         print(json.dumps({"other_configs": other_configs_leg(args.workload, device, args.steps)}))
         return
@@ -591,6 +628,8 @@ def main():
             out["gate_roofline"]["frac_of_device_ceiling"] = out["gate_roofline"]["achieved"] / hbm
     if want("ctc_head"):
         out["ctc_head_gate"] = ctc_head_leg(ctx, wl, device)
+    if want("qformer"):
+        out["qformer_pool"] = qformer_leg(ctx, wl, device)
     if want("library_gemm") and m.dtype == "bf16":
         out["library_gemm_reference"] = {"what": "torch.matmul (hipBLASLt) on the same shapes, IEEE half, plain GEMM without "
                                                  "the fused epilogues; compare with projection_tflops", "rows": fl["M"],

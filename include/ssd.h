@@ -105,8 +105,8 @@ int64_t ssd_inexact_weights(const ssd_ctx *ctx);
 
 /* Bytes of workspace needed for calls with at most max_frames CTC frames, max_tokens decoder rows
  * (sum over utterances of speech + prompt + draft), max_verify_rows draft tokens and max_utts
- * utterances (ctc_head_gate is covered once an output layer has been set: ask again after
- * ssd_set_ctc_head).  The workspace is a dev buffer, 256-byte aligned, handed over with
+ * utterances (ctc_head_gate and qformer_pool are covered once their weights have been set: ask again after
+ * ssd_set_ctc_head / ssd_set_qformer).  The workspace is a dev buffer, 256-byte aligned, handed over with
  * ssd_set_workspace and owned by the caller; it may be replaced between calls. */
 size_t ssd_workspace_bytes(const ssd_ctx *ctx, int64_t max_frames, int64_t max_tokens,
                            int64_t max_verify_rows, int64_t max_utts);
@@ -140,7 +140,8 @@ enum ssd_prof_class {
     SSD_PROF_GEMM_GATE_UP = 4, SSD_PROF_GEMM_DOWN = 5, SSD_PROF_LMHEAD = 6, SSD_PROF_OTHER = 7,
     SSD_PROF_AR = 8,          /* one span per ar_fallback call */
     SSD_PROF_CTC_HEAD = 9,    /* one span per ctc_head_gate call */
-    SSD_PROF_N_CLASSES = 10
+    SSD_PROF_QFORMER = 10,    /* one span per qformer_pool call */
+    SSD_PROF_N_CLASSES = 11
 };
 int ssd_profile_select(ssd_ctx *ctx, int kernel_class);
 /* Measurement aid: runs `iters` rounds of 16 independent v_mfma_f32_16x16x32_f16 per wavefront on
@@ -214,6 +215,30 @@ int ssd_set_ctc_head(ssd_ctx *ctx, const void *w_ctc, const float *bias, int V_c
 int ctc_head_gate(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*host*/, int B, int blank_id,
                   float tau_ctc, float *frame_entropy, int32_t *frame_argmax, float *max_entropy,
                   uint8_t *gate_pass, int32_t *draft_ctc, int32_t *draft_len);
+
+/* Sec. 3.1 (projector): the windowed cross-attention that turns encoder frames into the acoustic embeddings g of
+ * Sec. 2.2: every window of `window` (15) consecutive frames of an utterance is summarised by n_q (3) trainable
+ * queries, a downsampling by 5.  ssd_set_qformer copies the weights into the context (allocates device memory;
+ * waits for the stream; the caller's arrays may be released on return; a second call replaces the first):
+ *   q_proj dev [n_q, d_h] bf16       the queries after their query projection (constants of the model)
+ *   w_k, w_v dev [d_h, d_enc] bf16   key and value projections of the frames
+ *   w_o dev [d_out, d_h] bf16        output projection (d_out = d_model of the LLM)
+ * n_heads heads of d_h / n_heads dims, scores scaled by 1 / sqrt(d_head).  Limits: n_q <= 4, n_q * n_heads <= 64,
+ * window <= 32, d_h a multiple of 64 and of n_heads, d_enc of 64, d_out of 256 (SSD_ESHAPE otherwise).
+ * The key projection is folded into n_q * n_heads score rows at this point (the queries are constants).
+ *
+ * qformer_pool: for every utterance b and window w of its frames (the last one may be shorter and attends over
+ * the frames it has), query j: p = softmax over the window's frames of the head-wise scores, o = sum_t p_t w_v h_t,
+ * g = w_o o, written as bf16 to speech_emb row cu_speech[b] + n_q * w + j; cu_speech (host, B + 1 entries) is
+ * filled with the prefix sums S_b = n_q * ceil(T_b / window) that verify_forward takes.  The rest of a q-former
+ * layer (self-attention among the queries, feed-forward block, normalisation, second layer) is not described in
+ * the paper and not part of this call.
+ * enc_h: dev [cu_frames[B], d_enc] bf16 packed rows; speech_emb: dev [n_q * (frames / window + B), d_out] is enough.
+ * Needs the workspace ssd_workspace_bytes reports after ssd_set_qformer.  Errors: SSD_EINVAL, SSD_ESHAPE, SSD_EWORKSPACE. */
+int ssd_set_qformer(ssd_ctx *ctx, const void *q_proj, const void *w_k, const void *w_v, const void *w_o, int n_q,
+                    int n_heads, int d_h, int d_enc, int d_out, int window);
+int qformer_pool(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*host*/, int B, void *speech_emb,
+                 int32_t *cu_speech /*host, out*/);
 
 /* Between Sec. 2.1 and Sec. 2.2 (Eq. 7: only utterances that fail the entropy gate are verified).  Packs the
  * verification inputs of the n_sel selected utterances (sel: host, indices into the batch of B utterances, in

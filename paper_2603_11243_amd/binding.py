@@ -21,11 +21,11 @@ EXPORTS = ["ssd_create", "ssd_destroy", "ssd_workspace_bytes", "ssd_set_workspac
            "ssd_profile_select", "ssd_profile_read", "ssd_measure_mfma_ceiling", "ssd_measure_hbm_read", "ctc_gate", "verify_forward", "accept_prefix",
            "verify_forward_kv", "ssd_kv_cache_bytes", "ssd_set_kv_cache", "ssd_ar_workspace_bytes", "ar_fallback",
            "ssd_gate_grid", "ssd_accept_grid", "ssd_plan_batches", "ssd_set_ctc_head", "ctc_head_gate", "ssd_device_flags",
-           "ctc_gate_noalloc", "ssd_inexact_weights", "ssd_select_unconfident", "ssd_gather_i32"]
+           "ctc_gate_noalloc", "ssd_inexact_weights", "ssd_select_unconfident", "ssd_gather_i32", "ssd_set_qformer", "qformer_pool"]
 
 PROF_OFF, PROF_ALL = -2, -1
 PROF_CLASSES = ["gate", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lmhead_accept", "other",
-                "ar_fallback", "ctc_head_gate"]
+                "ar_fallback", "ctc_head_gate", "qformer_pool"]
 
 
 class SsdError(RuntimeError):
@@ -104,6 +104,10 @@ def load_library() -> C.CDLL:
     lib.ctc_gate_noalloc.restype = i32
     lib.ssd_select_unconfident.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.ssd_select_unconfident.restype = i32
+    lib.ssd_set_qformer.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32]
+    lib.ssd_set_qformer.restype = i32
+    lib.qformer_pool.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.qformer_pool.restype = i32
     lib.ssd_gather_i32.argtypes = [vp, vp, vp, i32, vp]
     lib.ssd_gather_i32.restype = i32
     lib.ssd_inexact_weights.argtypes = [vp]
@@ -328,6 +332,32 @@ class Context:
             out = torch.empty(len(ix), dtype=torch.int32, device=self.device)
         self._check(self._lib.ssd_gather_i32(self._h, _ptr(src), ix.ctypes.data, len(ix), _ptr(out)))
         return out
+
+    def set_qformer(self, q_proj: torch.Tensor, w_k: torch.Tensor, w_v: torch.Tensor, w_o: torch.Tensor, n_heads: int,
+                    window: int = 15):
+        """Projector windows (ssd_set_qformer): q_proj [n_q, d_h], w_k / w_v [d_h, d_enc], w_o [d_out, d_h], all bf16."""
+        for t in (q_proj, w_k, w_v, w_o):
+            if t.dtype != torch.bfloat16 or not t.is_contiguous():
+                raise ValueError("projector weights must be contiguous bfloat16 tensors")
+        n_q, d_h = int(q_proj.shape[0]), int(q_proj.shape[1])
+        d_enc, d_out = int(w_k.shape[1]), int(w_o.shape[0])
+        self._check(self._lib.ssd_set_qformer(self._h, _ptr(q_proj), _ptr(w_k), _ptr(w_v), _ptr(w_o), n_q, n_heads, d_h,
+                                              d_enc, d_out, window))
+        self._qformer = (n_q, d_enc, d_out, window)
+
+    def qformer_pool(self, enc_h: torch.Tensor, cu_frames, out: Optional[torch.Tensor] = None):
+        """Encoder frames -> acoustic embeddings (qformer_pool).  Returns (speech_emb [sum S, d_out] bf16, cu_speech)."""
+        n_q, d_enc, d_out, window = self._qformer
+        if enc_h.dtype != torch.bfloat16 or not enc_h.is_contiguous() or int(enc_h.shape[1]) != d_enc:
+            raise ValueError("enc_h must be a contiguous bfloat16 tensor with d_enc columns")
+        cu = _host_i32(cu_frames)
+        B = len(cu) - 1
+        n_rows = int(n_q * sum(-(-int(t) // window) for t in np.diff(cu)))
+        if out is None:
+            out = torch.empty((n_rows, d_out), dtype=torch.bfloat16, device=self.device)
+        cu_s = np.empty(B + 1, dtype=np.int32)
+        self._check(self._lib.qformer_pool(self._h, _ptr(enc_h), cu.ctypes.data, B, _ptr(out), cu_s.ctypes.data))
+        return out[:n_rows], cu_s
 
     def verify_forward(self, speech_emb: torch.Tensor, cu_speech, prompt_ids: torch.Tensor, cu_prompt,
                        draft_ids: torch.Tensor, cu_draft, out: Optional[torch.Tensor] = None,

@@ -99,6 +99,10 @@ struct ssd_ctx {
     uint16_t* head_w = nullptr;              // CTC output layer, padded with zero rows (bias -inf there)
     float* head_bias = nullptr;
     int head_V = 0, head_V_pad = 0, head_d = 0;
+    // projector windows (ssd_set_qformer): fused [scores | values] weight and the output projection, both bf16
+    uint16_t* qf_wcat = nullptr;
+    uint16_t* qf_wo = nullptr;
+    int qf_nq = 0, qf_heads = 0, qf_dh = 0, qf_denc = 0, qf_dout = 0, qf_window = 0;
     void* kv = nullptr;                      // caller-owned K/V cache: [layer][K|V][slots][d_kv] in the activation type
     int64_t kv_slots = 0;
     int64_t inexact_weights = 0;             // weight values the half conversion could not hold exactly
@@ -179,6 +183,18 @@ HeadPlan plan_head(int64_t frames, int64_t utts, int V) {
     p.arg = o; o = align_up(o + (size_t)frames * 4);
     p.cu = o; o = align_up(o + (size_t)(utts + 1) * 4);
     p.part = o; o = align_up(o + (size_t)frames * ctc_head_groups(V) * sizeof(float4));
+    p.total = o;
+    return p;
+}
+
+struct QformerPlan { size_t wins, kv, o, total; int64_t max_windows; };
+QformerPlan plan_qformer(int64_t frames, int64_t utts, int window, int n_q, int d_h) {
+    QformerPlan p;
+    p.max_windows = frames / window + utts;                  // every utterance may end in a short window
+    size_t o = 0;
+    p.wins = o; o = align_up(o + (size_t)p.max_windows * sizeof(QWindow));
+    p.kv = o; o = align_up(o + (size_t)frames * qformer_cat_rows(d_h) * 4);
+    p.o = o; o = align_up(o + (size_t)p.max_windows * n_q * d_h * 2);
     p.total = o;
     return p;
 }
@@ -417,6 +433,7 @@ size_t ssd_workspace_bytes(const ssd_ctx* ctx, int64_t max_frames, int64_t max_t
     if (!ctx || max_frames < 0 || max_tokens < 0 || max_verify_rows < 0 || max_utts < 0) return 0;
     size_t need = plan_gate(max_frames, max_utts).total;
     if (ctx->head_V) need = std::max(need, plan_head(max_frames, max_utts, ctx->head_V).total);
+    if (ctx->qf_nq) need = std::max(need, plan_qformer(max_frames, max_utts, ctx->qf_window, ctx->qf_nq, ctx->qf_dh).total);
     if (ctx->has_model) {
         need = std::max(need, plan_verify(ctx->cfg, max_tokens, max_verify_rows, max_utts).total);
         // a smaller batch may take the few-row path, which needs split-K scratch the big plan does not have
@@ -716,6 +733,79 @@ int ssd_set_ctc_head(ssd_ctx* ctx, const void* w_ctc, const float* bias, int V_c
     ctx->head_w = static_cast<uint16_t*>(w);
     ctx->head_bias = static_cast<float*>(b);
     ctx->head_V = V_ctc; ctx->head_V_pad = V_pad; ctx->head_d = d_enc;
+    return SSD_OK;
+}
+
+int ssd_set_qformer(ssd_ctx* ctx, const void* q_proj, const void* w_k, const void* w_v, const void* w_o, int n_q, int n_heads,
+                    int d_h, int d_enc, int d_out, int window) {
+    if (!ctx) return SSD_EINVAL;
+    if (!q_proj || !w_k || !w_v || !w_o) return fail(ctx, SSD_EINVAL, "ssd_set_qformer: NULL weight");
+    if (n_q <= 0 || n_heads <= 0 || d_h <= 0 || d_enc <= 0 || d_out <= 0 || window <= 0)
+        return fail(ctx, SSD_EINVAL, "ssd_set_qformer: non-positive size");
+    if (n_q > QF_MAX_QUERIES || n_q * n_heads > QF_SCORE_COLS || window > QF_MAX_WINDOW)
+        return fail(ctx, SSD_ESHAPE, "ssd_set_qformer: at most %d queries, %d (query, head) pairs and windows of %d frames",
+                    QF_MAX_QUERIES, QF_SCORE_COLS, QF_MAX_WINDOW);
+    if (d_h % n_heads || d_h % 64 || d_enc % 64 || d_out % 256)
+        return fail(ctx, SSD_ESHAPE, "ssd_set_qformer: d_h must be a multiple of n_heads and of 64, d_enc of 64, d_out of 256");
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    auto drop = [&](void* p) {
+        if (!p) return;
+        for (auto& q : ctx->owned) if (q == p) q = nullptr;
+        (void)hipFree(p);
+    };
+    drop(ctx->qf_wcat); drop(ctx->qf_wo);
+    ctx->qf_wcat = ctx->qf_wo = nullptr; ctx->qf_nq = 0;
+    void *wc = nullptr, *wo = nullptr;
+    HIP_TRY(ctx, hipMalloc(&wc, (size_t)qformer_cat_rows(d_h) * d_enc * 2));
+    ctx->owned.push_back(wc);
+    HIP_TRY(ctx, hipMalloc(&wo, (size_t)d_out * d_h * 2));
+    ctx->owned.push_back(wo);
+    launch_qformer_fold(static_cast<const uint16_t*>(q_proj), static_cast<const uint16_t*>(w_k), static_cast<const uint16_t*>(w_v),
+                        n_q, n_heads, d_h, d_enc, static_cast<uint16_t*>(wc), ctx->stream);
+    HIP_TRY(ctx, hipMemcpyAsync(wo, w_o, (size_t)d_out * d_h * 2, hipMemcpyDeviceToDevice, ctx->stream));
+    HIP_TRY(ctx, hipGetLastError());
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));     // the caller may release its copies on return
+    ctx->qf_wcat = static_cast<uint16_t*>(wc); ctx->qf_wo = static_cast<uint16_t*>(wo);
+    ctx->qf_nq = n_q; ctx->qf_heads = n_heads; ctx->qf_dh = d_h; ctx->qf_denc = d_enc; ctx->qf_dout = d_out; ctx->qf_window = window;
+    return SSD_OK;
+}
+
+int qformer_pool(ssd_ctx* ctx, const void* enc_h, const int32_t* cu_frames, int B, void* speech_emb, int32_t* cu_speech) {
+    if (!ctx) return SSD_EINVAL;
+    if (!ctx->qf_nq) return fail(ctx, SSD_EINVAL, "qformer_pool: no projector set (ssd_set_qformer)");
+    if (!enc_h || !cu_frames || !speech_emb || !cu_speech) return fail(ctx, SSD_EINVAL, "qformer_pool: NULL argument");
+    if (B <= 0) return fail(ctx, SSD_EINVAL, "qformer_pool: B must be positive (got %d)", B);
+    if (!check_cu(cu_frames, B, true))
+        return fail(ctx, SSD_EINVAL, "qformer_pool: cu_frames must start at 0 and increase strictly (every utterance needs a frame)");
+    const int64_t n_rows = cu_frames[B];
+    const int window = ctx->qf_window, n_q = ctx->qf_nq, d_h = ctx->qf_dh, d_enc = ctx->qf_denc;
+    if (n_rows * (int64_t)std::max(d_enc, d_h) * 2 >= ((int64_t)1 << 32))
+        return fail(ctx, SSD_ESHAPE, "qformer_pool: %lld frames exceed the 4 GiB an operand matrix may have; split the batch", (long long)n_rows);
+    const QformerPlan p = plan_qformer(n_rows, B, window, n_q, d_h);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+        return fail(ctx, SSD_EWORKSPACE, "qformer_pool: workspace of %zu bytes needed, %zu set", p.total, ctx->ws_bytes);
+    std::vector<QWindow> wins;
+    wins.reserve((size_t)p.max_windows);
+    cu_speech[0] = 0;
+    for (int b = 0; b < B; ++b) {
+        for (int f = cu_frames[b]; f < cu_frames[b + 1]; f += window)
+            wins.push_back(QWindow{f, std::min(window, cu_frames[b + 1] - f)});
+        cu_speech[b + 1] = (int32_t)(wins.size() * n_q);
+    }
+    const int n_windows = (int)wins.size();
+    char* ws = static_cast<char*>(ctx->ws);
+    int rc = upload(ctx, wins.data(), ws + p.wins, wins.size() * sizeof(QWindow));
+    if (rc != SSD_OK) return rc;
+    float* kv = reinterpret_cast<float*>(ws + p.kv);
+    uint16_t* o = reinterpret_cast<uint16_t*>(ws + p.o);
+    const int n_cat = qformer_cat_rows(d_h);
+    {
+        ProfScope ps(ctx, SSD_PROF_QFORMER);
+        launch_gemm_store_f32(static_cast<const uint16_t*>(enc_h), ctx->qf_wcat, kv, (int)n_rows, n_cat, d_enc, true, ctx->stream);
+        launch_qformer_pool(kv, n_cat, reinterpret_cast<const QWindow*>(ws + p.wins), n_windows, n_q, ctx->qf_heads, d_h, o, ctx->stream);
+        launch_gemm_store_16(o, ctx->qf_wo, static_cast<uint16_t*>(speech_emb), n_windows * n_q, ctx->qf_dout, d_h, true, ctx->stream);
+    }
+    HIP_TRY(ctx, hipGetLastError());
     return SSD_OK;
 }
 

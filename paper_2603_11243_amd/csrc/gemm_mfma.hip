@@ -227,6 +227,43 @@ struct EpiPartial {
     }
 };
 
+// Plain stores for products outside the decoder layer (the projector's windowed cross-attention): the
+// accumulator as fp32, or rounded to the operand type, into rows of ldc elements.
+template <bool BF_>
+struct EpiStoreF32 {
+    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    float* c; int ldc;
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < L::REGS; ++r) {
+                const int row = row0 + L::row(i, r, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) c[(int64_t)row * ldc + col0 + L::col(j, lane)] = acc[i][j][r];
+            }
+    }
+};
+template <bool BF_>
+struct EpiStore16 {
+    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    uint16_t* c; int ldc;
+    template <int TM, int TN, class L = Layout32>
+    __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < L::REGS; ++r) {
+                const int row = row0 + L::row(i, r, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) c[(int64_t)row * ldc + col0 + L::col(j, lane)] = Op16<BF>::cvt(acc[i][j][r]);
+            }
+    }
+};
+
 // grid = tiles * splits; split s of a tile accumulates K slices [s*KT/splits, (s+1)*KT/splits)
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
@@ -442,6 +479,15 @@ int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_str
                          float descale, bool bf16_ops, hipStream_t st) {
     return bf16_ops ? gemm_residual_impl<true>(A, W, W_stream, x, partials, M, N, K, descale, st)
                     : gemm_residual_impl<false>(A, W, W_stream, x, partials, M, N, K, descale, st);
+}
+
+void launch_gemm_store_f32(const uint16_t* A, const uint16_t* W, float* C, int M, int N, int K, bool bf16_ops, hipStream_t st) {
+    if (bf16_ops) launch_by_shape(A, W, nullptr, M, N, K, EpiStoreF32<true>{C, N}, st);
+    else launch_by_shape(A, W, nullptr, M, N, K, EpiStoreF32<false>{C, N}, st);
+}
+void launch_gemm_store_16(const uint16_t* A, const uint16_t* W, uint16_t* C, int M, int N, int K, bool bf16_ops, hipStream_t st) {
+    if (bf16_ops) launch_by_shape(A, W, nullptr, M, N, K, EpiStore16<true>{C, N}, st);
+    else launch_by_shape(A, W, nullptr, M, N, K, EpiStore16<false>{C, N}, st);
 }
 
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,

@@ -30,6 +30,21 @@ void launch_ctc_head_pack(const uint16_t* w, const float* bias, int V, int V_pad
 void launch_ctc_head(const uint16_t* enc_h, const uint16_t* w_pad, const float* bias_pad, int n_rows, int d_enc, int V,
                      int V_pad, float4* part, float* H, int32_t* arg, hipStream_t st);
 
+// ---- qformer.hip: windowed cross-attention of the projector (Sec. 3.1)
+constexpr int QF_SCORE_COLS = 64;    // columns of the fused weight that hold the folded (query, head) score rows
+constexpr int QF_MAX_WINDOW = 32;
+constexpr int QF_MAX_QUERIES = 4;
+struct QWindow { int32_t frame0, n_frames; };
+int qformer_cat_rows(int d_h);       // rows of the fused [scores | values] weight, padded to a multiple of 256
+// w_cat [qformer_cat_rows(d_h), d_enc] bf16: rows j * n_heads + h hold w_k[head h]^T q_proj[j, head h] / sqrt(d_head),
+// rows 64 .. 64 + d_h - 1 hold w_v, the rest is zero
+void launch_qformer_fold(const uint16_t* q_proj, const uint16_t* w_k, const uint16_t* w_v, int n_q, int n_heads, int d_h,
+                         int d_enc, uint16_t* w_cat, hipStream_t st);
+// kv [frames, ldkv] fp32 = enc_h w_cat^T; for every window: softmax of its score columns over its frames, then the
+// weighted sum of its value columns: o [n_windows * n_q, d_h] bf16
+void launch_qformer_pool(const float* kv, int ldkv, const QWindow* wins, int n_windows, int n_q, int n_heads, int d_h,
+                         uint16_t* o, hipStream_t st);
+
 // ---- row metadata built on the host for one verify_forward call
 // src code of a decoder row: speech rows hold the speech_emb row index; token rows hold
 // SRC_PROMPT | index into prompt_ids or SRC_DRAFT | index into draft_ids.
@@ -92,6 +107,10 @@ int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_str
                          float descale, bool bf16_ops, hipStream_t st);
 void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const void* W_stream, uint16_t* h, int M, int d_ff, int K,
                         float descale, int32_t* flags, bool bf16_ops, hipStream_t st);
+// plain products C[M,N] = A[M,K] W[N,K]^T with fp32 accumulation, stored as fp32 or rounded to the operand type
+// (N % 256 == 0, K % 64 == 0, row-major 16-bit operands of the type bf16_ops selects)
+void launch_gemm_store_f32(const uint16_t* A, const uint16_t* W, float* C, int M, int N, int K, bool bf16_ops, hipStream_t st);
+void launch_gemm_store_16(const uint16_t* A, const uint16_t* W, uint16_t* C, int M, int N, int K, bool bf16_ops, hipStream_t st);
 // second copy of an f16 weight matrix W[N,K] for the few-row kernel (N % 64 == 0, K % 256 == 0)
 bool stream_layout_supported(int N, int K);
 void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_t st);

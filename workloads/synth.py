@@ -215,3 +215,16 @@ def make_verify_inputs(wl: Workload, seconds: np.ndarray, drafts: List[np.ndarra
     gen.manual_seed(seed * 7919 + 13)
     emb = _randn((int(cu_s[-1]), m.d_model), 0.02, _TORCH_DTYPE[m.dtype], gen, device)
     return VerifyInputs(emb, cu_s, prompt, cu_p, dr, cu_d)
+
+
+def make_qformer_weights(seed: int, n_q: int = 3, d_h: int = 1024, d_enc: int = 1024, d_out: int = 2048, device="cpu") -> dict:
+    """Weights of the projector's windowed cross-attention, bf16: projected queries N(0,1), key / value
+    projections N(0, 1/d_enc), output projection N(0, 1/d_h) (scores and outputs of order one on unit-variance
+    encoder states)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed * 7919 + 17)
+    dt = torch.bfloat16
+    return {"q_proj": _randn((n_q, d_h), 1.0, dt, gen, device),
+            "w_k": _randn((d_h, d_enc), 1.0 / math.sqrt(d_enc), dt, gen, device),
+            "w_v": _randn((d_h, d_enc), 1.0 / math.sqrt(d_enc), dt, gen, device),
+            "w_o": _randn((d_out, d_h), 1.0 / math.sqrt(d_h), dt, gen, device)}
