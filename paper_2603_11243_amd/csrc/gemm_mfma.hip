@@ -394,7 +394,12 @@ void launch_stream_layout(const uint16_t* w, void* out, int N, int K, hipStream_
 template <class Epi>
 static void launch_skinny(const f16_t* A, const f16_t* W, const void* Ws, int M, int N, int K, int splits, const Epi& epi, hipStream_t st) {
     if (try_launch_stream(A, Ws, M, N, K, splits, epi, st)) return;
-    if (M <= 32) launch_gemm<32, 64, 1, 1, 6>(A, W, M, N, K, splits, epi, st);
+    // 33..128 rows: the launch should put a workgroup on every CU.  A projection with few column tiles and no K
+    // split (QKV: 64-80 tiles) is cut into row tiles of 32 or 64 as well; the row tiles of a column slab then
+    // read the same weights, which the L2 serves.
+    const int col_tiles = (N / 64) * splits;
+    if (M <= 32 || (col_tiles <= 96 && M > 32)) launch_gemm<32, 64, 1, 1, 6>(A, W, M, N, K, splits, epi, st);
+    else if (col_tiles <= 160 && M > 64) launch_gemm<64, 64, 2, 1, 6>(A, W, M, N, K, splits, epi, st);
     else launch_gemm<128, 64, 4, 1, 6>(A, W, M, N, K, splits, epi, st);
 }
 
