@@ -494,24 +494,27 @@ __global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* __restrict__ s
     sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
-// Streaming read of n 16-byte units: every workgroup (eight wavefronts) walks its own contiguous share,
-// 64 KB per trip (eight 1 KB loads in flight per wavefront); the values are folded into a word that is
-// stored only if it has a particular value (so the loads cannot be dropped).
+// Streaming read of n 16-byte units, the access pattern that reads fastest on this chip: all wavefronts of the
+// launch interleave 8 KB trips (eight 1 KB loads in flight per wavefront, consecutive wavefronts on consecutive
+// trips) and the loads carry the non-temporal hint.  (Measured on 3 GiB: 7.0 TB/s; the same loop without the hint
+// 6.2 TB/s, a contiguous share per workgroup 6.0 TB/s without and 6.6 TB/s with the hint.)  The values are folded
+// into a word that is stored only if it has a particular value, so the loads cannot be dropped.
 __global__ void __launch_bounds__(512) hbm_read_kernel(const uint4* __restrict__ p, int64_t n, uint32_t* __restrict__ sink) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4* q = reinterpret_cast<const u32x4*>(p);
     uint32_t acc = 0;
-    const int64_t per_wg = (n + gridDim.x - 1) / gridDim.x;
-    const int64_t lo = (int64_t)blockIdx.x * per_wg, hi = min(n, lo + per_wg);
     const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-    int64_t i = lo + wave * 512 + lane;                      // a wavefront's trip: 8 x 64 units
-    for (; i + 7 * 64 < hi; i += 8 * 512) {
-        uint4 v[8];
+    const int64_t gw = (int64_t)blockIdx.x * 8 + wave, nw = (int64_t)gridDim.x * 8;
+    int64_t i = gw * 512 + lane;
+    for (; i + 7 * 64 < n; i += nw * 512) {
+        u32x4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = p[i + u * 64];
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(q + i + u * 64);
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (int u = 0; u < 8; ++u)
-        if (i + u * 64 < hi) { const uint4 v = p[i + u * 64]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+        if (i + u * 64 < n) { const u32x4 v = q[i + u * 64]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
     if (acc == 0x9e3779b9u) *sink = acc;
 }
 void launch_hbm_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st) {
