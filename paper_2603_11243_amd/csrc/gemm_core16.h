@@ -25,19 +25,34 @@ namespace ssd {
 
 // Row / column of accumulator register r of 16x16 block (i, j) for this lane, relative to the wave tile.
 struct Layout16 {
+    static constexpr bool TRANSPOSED = false;
     static constexpr int BLOCK = 16, REGS = 4, PAIR = 2;     // PAIR: blocks between a column and the one 32 further
     typedef f32x4_t vec_t;
     static __device__ __forceinline__ int row(int i, int r, int lane) { return i * 16 + 4 * (lane / 16) + r; }
     static __device__ __forceinline__ int col(int j, int lane) { return j * 16 + (lane % 16); }
 };
+// Transposed 16x16 blocks: the MFMA is issued with the operands swapped (W fragment as the row operand), so a lane
+// holds ONE row (lane % 16 of the block) and FOUR CONSECUTIVE columns 4 (lane / 16) + r.  In row-major output that
+// is one 16-byte (fp32) or 8-byte (half) access per lane and block instead of four 4- or 2-byte ones: the epilogues
+// issue a quarter of the memory instructions.
+struct Layout16T {
+    static constexpr int BLOCK = 16, REGS = 4, PAIR = 2;
+    static constexpr bool TRANSPOSED = true;
+    typedef f32x4_t vec_t;
+    static __device__ __forceinline__ int row(int i, int lane) { return i * 16 + (lane % 16); }
+    static __device__ __forceinline__ int col4(int j, int lane) { return j * 16 + 4 * (lane / 16); }    // first of four
+};
 struct Layout32 {
+    static constexpr bool TRANSPOSED = false;
     static constexpr int BLOCK = 32, REGS = 16, PAIR = 1;
     typedef f32x16_t vec_t;
     static __device__ __forceinline__ int row(int i, int r, int lane) { return acc_row(i, r, lane); }
     static __device__ __forceinline__ int col(int j, int lane) { return acc_col(j, lane); }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool BF16 = false>
+// SWAP: issue the MFMA with the W fragment as the row operand, which transposes every accumulator block
+// (Layout16T instead of Layout16); the loop, the fragments and their reads are the same.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool BF16 = false, bool SWAP = false>
 struct GemmTile16 {
     static constexpr int NSTAGE = 2;
     static constexpr int WAVES = WAVES_M * WAVES_N;
@@ -109,7 +124,8 @@ struct GemmTile16 {
             for (int i = 0; i < TH; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[half * TH + i][j] = mfma_16x16x32<BF16>(a[i], b[j], acc[half * TH + i][j]);
+                    acc[half * TH + i][j] = SWAP ? mfma_16x16x32<BF16>(b[j], a[i], acc[half * TH + i][j])
+                                                 : mfma_16x16x32<BF16>(a[i], b[j], acc[half * TH + i][j]);
         };
         // scheduling patterns: one MFMA, one LDS read, for the first n_reads MFMAs of a phase
         constexpr int PH = TH * TN;                          // MFMAs per phase

@@ -48,10 +48,40 @@ constexpr int residual_batch(int tm, int g0) {             // largest divisor of
 }
 template <bool BF_>
 struct EpiResidual {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    // (not transposed: the fp32 read-modify-write measured 3-8 % slower with 16-byte accesses whose lanes of one
+    // row segment are 16 lane ids apart, O projection 8.77 -> 8.95 ms per step at 15214 rows)
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = false;
     float* x; int ldx; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        if constexpr (L::TRANSPOSED) {
+            // a lane holds four consecutive columns of one row per block: 16-byte loads and stores
+            constexpr int GT = residual_batch(TM, 96 / (4 * TN));
+#pragma unroll
+            for (int i0 = 0; i0 < TM; i0 += GT) {
+                float4 old[GT][TN];
+#pragma unroll
+                for (int g = 0; g < GT; ++g) {
+                    const int row = min(row0 + L::row(i0 + g, lane), M - 1);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        old[g][j] = *reinterpret_cast<const float4*>(x + (int64_t)row * ldx + col0 + L::col4(j, lane));
+                }
+#pragma unroll
+                for (int g = 0; g < GT; ++g) {
+                    const int row = row0 + L::row(i0 + g, lane);
+                    if (row >= M) continue;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const f32x4_t a = acc[i0 + g][j];
+                        *reinterpret_cast<float4*>(x + (int64_t)row * ldx + col0 + L::col4(j, lane)) =
+                            make_float4(old[g][j].x + a[0] * descale, old[g][j].y + a[1] * descale, old[g][j].z + a[2] * descale,
+                                        old[g][j].w + a[3] * descale);
+                    }
+                }
+            }
+            return;
+        } else {
         // Row blocks per batch: all loads of a batch are in flight together, so a tile pays one memory
         // latency per batch.  Up to 96 registers of old values (the fragment registers are dead by now).
         constexpr int G0 = 96 / (L::REGS * TN);
@@ -78,12 +108,13 @@ struct EpiResidual {
                         x[(int64_t)row * ldx + col0 + L::col(j, lane)] = old[g][r][j] + acc[i0 + g][j][r] * descale;
                 }
         }
+        }
     }
 };
 
 template <bool BF_>
 struct EpiQkvRope {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;     // big tiles: transposed accumulator blocks
     f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
@@ -95,6 +126,85 @@ struct EpiQkvRope {
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert((TN * L::BLOCK) % 64 == 0, "rotation partners live 32 packed columns apart in groups of 64");
+        if constexpr (L::TRANSPOSED) {
+            // A lane holds one row and four consecutive packed columns per block: the four rotary entries are one
+            // 32-byte read, the outputs two 8-byte stores (and two more into the K/V cache).
+            const float2* tabT = rope_rows ? rope_rows : rope_tab;
+            const int d_kvT = d_rot - d_q;
+            float peak = 0.f;
+            constexpr int NJT = TN / 2;
+            constexpr int GT = residual_batch(TM, 64 / (NJT * 8) > 0 ? 64 / (NJT * 8) : 1);
+#pragma unroll
+            for (int i0 = 0; i0 < TM; i0 += GT) {
+                int t_row[GT], slot[GT];
+#pragma unroll
+                for (int g = 0; g < GT; ++g) {
+                    const int row = min(row0 + L::row(i0 + g, lane), M - 1);
+                    t_row[g] = rope_rows ? row : pos[row];
+                    slot[g] = row_slot ? row_slot[row] : -1;
+                }
+                float4 cs[GT][NJT][2];                      // (cos, sin) of four consecutive rotary indices
+#pragma unroll
+                for (int g = 0; g < GT; ++g)
+#pragma unroll
+                    for (int jj = 0; jj < NJT; ++jj) {
+                        const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
+                        const int p = col0 + j * L::BLOCK;
+                        const int i_rot = ((p % 128) / 64) * 32 + p % 32 + 4 * (lane / 16);
+                        if (p < d_rot) {
+                            const float4* src = reinterpret_cast<const float4*>(tabT + (int64_t)t_row[g] * 64 + i_rot);
+                            cs[g][jj][0] = src[0];
+                            cs[g][jj][1] = src[1];
+                        } else {
+                            cs[g][jj][0] = cs[g][jj][1] = make_float4(1.f, 0.f, 1.f, 0.f);
+                        }
+                    }
+                auto store_batch = [&](auto clamp_c) {
+                    constexpr bool CLAMP = decltype(clamp_c)::value;
+#pragma unroll
+                    for (int g = 0; g < GT; ++g) {
+                        const int row = row0 + L::row(i0 + g, lane);
+                        if (row >= M) continue;
+#pragma unroll
+                        for (int jj = 0; jj < NJT; ++jj) {
+                            const int j = (jj / L::PAIR) * 2 * L::PAIR + jj % L::PAIR;
+                            const int p = col0 + j * L::BLOCK;
+                            const bool rot = p < d_rot;
+                            const int head = p / 128, i_rot = ((p % 128) / 64) * 32 + p % 32 + 4 * (lane / 16);
+                            const int c0 = rot ? head * 128 + i_rot : p + 4 * (lane / 16);
+                            const int c1 = rot ? c0 + 64 : c0 + 32;
+                            const f32x4_t a = acc[i0 + g][j], b = acc[i0 + g][j + L::PAIR];
+                            const float cx[4] = {cs[g][jj][0].x, cs[g][jj][0].z, cs[g][jj][1].x, cs[g][jj][1].z};
+                            const float sy[4] = {cs[g][jj][0].y, cs[g][jj][0].w, cs[g][jj][1].y, cs[g][jj][1].w};
+                            uint16_t v0[4], v1[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float av = a[r] * descale, bv = b[r] * descale;
+                                v0[r] = Op16<BF>::template store<CLAMP>(av * cx[r] - bv * sy[r], peak);
+                                v1[r] = Op16<BF>::template store<CLAMP>(bv * cx[r] + av * sy[r], peak);
+                            }
+                            const uint2 w0 = make_uint2((uint32_t)v0[0] | ((uint32_t)v0[1] << 16), (uint32_t)v0[2] | ((uint32_t)v0[3] << 16));
+                            const uint2 w1 = make_uint2((uint32_t)v1[0] | ((uint32_t)v1[1] << 16), (uint32_t)v1[2] | ((uint32_t)v1[3] << 16));
+                            f16_t* o = qkv + (int64_t)row * ldq;
+                            *reinterpret_cast<uint2*>(o + c0) = w0;
+                            *reinterpret_cast<uint2*>(o + c1) = w1;
+                            if (slot[g] >= 0 && c0 >= d_q) {
+                                f16_t* dst = (rot ? kc : vc) + (int64_t)slot[g] * d_kvT - (rot ? d_q : d_rot);
+                                *reinterpret_cast<uint2*>(dst + c0) = w0;
+                                *reinterpret_cast<uint2*>(dst + c1) = w1;
+                            }
+                        }
+                    }
+                };
+                const float before = peak;
+                store_batch(std::false_type());
+                if (!(peak <= F16_MAX)) {
+                    peak = before;
+                    store_batch(std::true_type());
+                    raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
+                }
+            }
+        } else {
         // Column blocks come in groups of 64 packed columns: the first half holds x[i], the second x[i+64]
         // of 32 rotation pairs (or 64 plain columns of v); block j is handled with its partner j + PAIR.
         constexpr int NJ = TN / 2;
@@ -167,17 +277,48 @@ struct EpiQkvRope {
                 raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
             }
         }
+        }
     }
 };
 
 template <bool BF_>
 struct EpiSwiglu {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
     f16_t* h; int d_ff; float descale; int32_t* flags;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
         static_assert((TN * L::BLOCK) % 64 == 0, "gate/up live 32 packed columns apart in groups of 64");
         float peak = 0.f;                                   // largest magnitude stored by this lane
+        if constexpr (L::TRANSPOSED) {
+            // a lane holds one row and four consecutive packed columns per block: four outputs, one 8-byte store
+            auto store_allT = [&](auto clamp_c) {
+                constexpr bool CLAMP = decltype(clamp_c)::value;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int row = row0 + L::row(i, lane);
+                    if (row >= M) continue;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if ((j / L::PAIR) % 2 != 0) continue;
+                        const int p = col0 + j * L::BLOCK;
+                        const int f = (p / 64) * 32 + p % 32 + 4 * (lane / 16);
+                        uint16_t v[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float g = acc[i][j][r] * descale, u = acc[i][j + L::PAIR][r] * descale;
+                            v[r] = Op16<BF>::template store<CLAMP>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)), peak);
+                        }
+                        *reinterpret_cast<uint2*>(h + (int64_t)row * d_ff + f) =
+                            make_uint2((uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
+                    }
+                }
+            };
+            store_allT(std::false_type());
+            if (!(peak <= F16_MAX)) {
+                store_allT(std::true_type());
+                raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
+            }
+        } else {
         auto store_all = [&](auto clamp_c) {
             constexpr bool CLAMP = decltype(clamp_c)::value;
 #pragma unroll
@@ -203,6 +344,7 @@ struct EpiSwiglu {
             store_all(std::true_type());
             raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
         }
+        }
     }
 };
 
@@ -210,7 +352,7 @@ struct EpiSwiglu {
 // Whoever consumes it (the RMSNorm that follows) adds the splits in a fixed order.
 template <bool BF_>
 struct EpiPartial {
-    static constexpr bool WANTS_SPLIT = true, BF = BF_;
+    static constexpr bool WANTS_SPLIT = true, BF = BF_, TRANSPOSE = false;
     float* part; int ld; int64_t split_stride; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
@@ -231,10 +373,22 @@ struct EpiPartial {
 // accumulator as fp32, or rounded to the operand type, into rows of ldc elements.
 template <bool BF_>
 struct EpiStoreF32 {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
     float* c; int ldc;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        if constexpr (L::TRANSPOSED) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = row0 + L::row(i, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    *reinterpret_cast<float4*>(c + (int64_t)row * ldc + col0 + L::col4(j, lane)) =
+                        make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            }
+            return;
+        } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -244,14 +398,27 @@ struct EpiStoreF32 {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) c[(int64_t)row * ldc + col0 + L::col(j, lane)] = acc[i][j][r];
             }
+        }
     }
 };
 template <bool BF_>
 struct EpiStore16 {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
     uint16_t* c; int ldc;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        if constexpr (L::TRANSPOSED) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = row0 + L::row(i, lane);
+                if (row >= M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    *reinterpret_cast<uint2*>(c + (int64_t)row * ldc + col0 + L::col4(j, lane)) =
+                        make_uint2(op_pack2<BF>(acc[i][j][0], acc[i][j][1]), op_pack2<BF>(acc[i][j][2], acc[i][j][3]));
+            }
+            return;
+        } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -261,6 +428,7 @@ struct EpiStore16 {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) c[(int64_t)row * ldc + col0 + L::col(j, lane)] = Op16<BF>::cvt(acc[i][j][r]);
             }
+        }
     }
 };
 
@@ -310,7 +478,7 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
 template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 gemm_mfma16_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
-    using Tile = GemmTile16<BM, BN, WAVES_M, WAVES_N, Epi::BF>;
+    using Tile = GemmTile16<BM, BN, WAVES_M, WAVES_N, Epi::BF, Epi::TRANSPOSE>;   // transposed accumulator blocks where the epilogue gains from them
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
     int tm, tn;
@@ -325,7 +493,10 @@ gemm_mfma16_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int
     Tile::run(A, W, M, K, tm * BM, tn * BN, 0, K / GEMM_BK, smem_raw, acc);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    epi.template operator()<Tile::TM, Tile::TN, Layout16>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
+    if constexpr (Epi::TRANSPOSE)
+        epi.template operator()<Tile::TM, Tile::TN, Layout16T>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
+    else
+        epi.template operator()<Tile::TM, Tile::TN, Layout16>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
