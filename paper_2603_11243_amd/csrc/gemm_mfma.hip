@@ -50,7 +50,7 @@ template <bool BF_>
 struct EpiResidual {
     // (not transposed: the fp32 read-modify-write measured 3-8 % slower with 16-byte accesses whose lanes of one
     // row segment are 16 lane ids apart, O projection 8.77 -> 8.95 ms per step at 15214 rows)
-    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = false;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = false, USES_LDS = false;
     float* x; int ldx; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -112,9 +112,61 @@ struct EpiResidual {
     }
 };
 
+// The residual epilogue of the big tiles: x[M,N] += acc through the workgroup's LDS (free after the K loop).  With
+// transposed accumulator blocks a lane writes its four consecutive columns of a row as one 16-byte LDS store; the
+// wavefront's 64 x 64 half tile is then read back row by row, 16 lanes per 256-byte row, so that the old values of x
+// are loaded and the sums stored with fully coalesced 16-byte accesses: 32 + 32 global instructions per wavefront
+// instead of 128 + 128 four-byte ones that touch 64-byte pieces of four rows each.
+constexpr int RES_LDS_STRIDE = 68;                           // floats per staged row: 64 + 4 (16-byte columns stay spread)
+template <bool BF_>
+struct EpiResidualLds {
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = true;
+    float* x; int ldx; float descale;
+    template <int TM> static constexpr int wave_lds_bytes() { return (TM / 2) * 16 * RES_LDS_STRIDE * 4; }
+    template <int TM, int TN>
+    __device__ __forceinline__ void run_lds(f32x4_t (&acc)[TM][TN], int row0, int col0, int M, int lane, float* stage) const {
+        static_assert(TN == 4 && TM % 2 == 0, "a wavefront tile of 64 columns, two halves of row blocks");
+        constexpr int HB = TM / 2;                           // row blocks per half
+        constexpr int ROWS = HB * 16;                        // rows per half
+        constexpr int NI = ROWS / 4;                         // instructions per half: 4 rows x 256 bytes each
+        const int m = lane % 16, g = lane / 16;
+        const int rr = lane / 16, cc = (lane % 16) * 4;      // read-back: row 4 it + rr of the half, columns cc .. cc + 3
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            // old values first: their round trip overlaps the LDS exchange
+            float4 old[NI];
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int row = min(row0 + half * ROWS + 4 * it + rr, M - 1);
+                old[it] = *reinterpret_cast<const float4*>(x + (int64_t)row * ldx + col0 + cc);
+            }
+            if (half) __builtin_amdgcn_wave_barrier();       // the reads of the first half are done (waited for below)
+#pragma unroll
+            for (int i = 0; i < HB; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const f32x4_t a = acc[half * HB + i][j];
+                    *reinterpret_cast<float4*>(stage + (i * 16 + m) * RES_LDS_STRIDE + j * 16 + 4 * g) =
+                        make_float4(a[0] * descale, a[1] * descale, a[2] * descale, a[3] * descale);
+                }
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): the stores have landed
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < NI; ++it) {
+                const int row = row0 + half * ROWS + 4 * it + rr;
+                const float4 v = *reinterpret_cast<const float4*>(stage + (4 * it + rr) * RES_LDS_STRIDE + cc);
+                if (row < M)
+                    *reinterpret_cast<float4*>(x + (int64_t)row * ldx + col0 + cc) =
+                        make_float4(old[it].x + v.x, old[it].y + v.y, old[it].z + v.z, old[it].w + v.w);
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+        }
+    }
+};
+
 template <bool BF_>
 struct EpiQkvRope {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;     // big tiles: transposed accumulator blocks
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = false;     // big tiles: transposed accumulator blocks
     f16_t* qkv; int ldq; int d_rot; float descale;            // d_rot = d_q + d_kv: columns that get rotated
     const int32_t* pos; const float2* rope_tab; // rope_tab[pos][i] = (cos, sin), i < 64
     // optional K/V cache: rows with row_slot[row] >= 0 also store their k and v parts at that slot
@@ -283,7 +335,7 @@ struct EpiQkvRope {
 
 template <bool BF_>
 struct EpiSwiglu {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = false;
     f16_t* h; int d_ff; float descale; int32_t* flags;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -352,7 +404,7 @@ struct EpiSwiglu {
 // Whoever consumes it (the RMSNorm that follows) adds the splits in a fixed order.
 template <bool BF_>
 struct EpiPartial {
-    static constexpr bool WANTS_SPLIT = true, BF = BF_, TRANSPOSE = false;
+    static constexpr bool WANTS_SPLIT = true, BF = BF_, TRANSPOSE = false, USES_LDS = false;
     float* part; int ld; int64_t split_stride; float descale;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane, int split) const {
@@ -373,7 +425,7 @@ struct EpiPartial {
 // accumulator as fp32, or rounded to the operand type, into rows of ldc elements.
 template <bool BF_>
 struct EpiStoreF32 {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = false;
     float* c; int ldc;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -403,7 +455,7 @@ struct EpiStoreF32 {
 };
 template <bool BF_>
 struct EpiStore16 {
-    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true;
+    static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = false;
     uint16_t* c; int ldc;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
@@ -493,7 +545,10 @@ gemm_mfma16_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int
     Tile::run(A, W, M, K, tm * BM, tn * BN, 0, K / GEMM_BK, smem_raw, acc);
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    if constexpr (Epi::TRANSPOSE)
+    if constexpr (Epi::USES_LDS)
+        epi.template run_lds<Tile::TM, Tile::TN>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane,
+                                                 reinterpret_cast<float*>(smem_raw + wave * Epi::template wave_lds_bytes<Tile::TM>()));
+    else if constexpr (Epi::TRANSPOSE)
         epi.template operator()<Tile::TM, Tile::TN, Layout16T>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
     else
         epi.template operator()<Tile::TM, Tile::TN, Layout16>(acc, tm * BM + wm * Tile::WTM, tn * BN + wn * Tile::WTN, M, lane);
@@ -503,7 +558,16 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
 static void launch_gemm16(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
     if (M <= 0) return;
     auto kern = gemm_mfma16_kernel<BM, BN, WAVES_M, WAVES_N, Epi>;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, 2>();
+    constexpr size_t ring = gemm_lds_bytes<BM, BN, 2>();
+    constexpr size_t lds = [] {
+        if constexpr (Epi::USES_LDS) {
+            constexpr size_t stage = (size_t)WAVES_M * WAVES_N * Epi::template wave_lds_bytes<BM / WAVES_M / 16>();
+            return stage > ring ? stage : ring;
+        } else {
+            return ring;
+        }
+    }();
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -575,8 +639,7 @@ static void launch_skinny(const f16_t* A, const f16_t* W, const void* Ws, int M,
 }
 
 template <class Epi>
-static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int M, int N, int K, const Epi& epi, hipStream_t st) {
-    if (M <= SKINNY_MAX_ROWS) { launch_skinny(A, W, Ws, M, N, K, 1, epi, st); return; }
+static void launch_big(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
     const int heights[3] = {256, 192, 128};
     const double eff[3] = {1.0, 0.97, 0.90};
     int best = 0;
@@ -589,6 +652,11 @@ static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int 
     if (best == 0) launch_gemm16<256, 256, 2, 4>(A, W, M, N, K, epi, st);
     else if (best == 1) launch_gemm16<192, 256, 2, 4>(A, W, M, N, K, epi, st);
     else launch_gemm16<128, 256, 2, 4>(A, W, M, N, K, epi, st);
+}
+template <class Epi>
+static void launch_by_shape(const f16_t* A, const f16_t* W, const void* Ws, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= SKINNY_MAX_ROWS) launch_skinny(A, W, Ws, M, N, K, 1, epi, st);
+    else launch_big(A, W, M, N, K, epi, st);
 }
 
 void launch_gemm_qkv_rope(const uint16_t* A, const uint16_t* Wqkv_packed, const void* W_stream, uint16_t* qkv, const int32_t* pos,
@@ -647,8 +715,8 @@ static int gemm_residual_impl(const uint16_t* A, const uint16_t* W, const void* 
         launch_skinny(A, W, W_stream, M, N, K, splits, epi, st);
         return splits;
     }
-    EpiResidual<BF> epi{x, N, descale};
-    launch_by_shape(A, W, W_stream, M, N, K, epi, st);
+    if (M > SKINNY_MAX_ROWS) launch_big(A, W, M, N, K, EpiResidualLds<BF>{x, N, descale}, st);
+    else launch_skinny(A, W, W_stream, M, N, K, 1, EpiResidual<BF>{x, N, descale}, st);
     return 1;
 }
 int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_stream, float* x, float* partials, int M, int N, int K,
