@@ -39,9 +39,9 @@ LEGS = ["main", "cpu_baseline", "mfma_ceiling", "hbm_ceiling", "ar_fallback", "g
 # of the kernel on M rows), each scaled by what the same counter reads for a plain 1 GiB device copy
 # (`--copy-reference`).  Every entry names the committed summary it was read from.
 MEASURED_TRAFFIC = {
-    "cfg5_3b_ragged128": {"bytes": (1082151.4 * 2.0 + 263288.6 * 1.0) * 1024.0,    # average launch (full layers and the last layer's)
+    "cfg5_3b_ragged128": {"bytes": (1082119.7 * 2.0 + 238759.3 * 1.0) * 1024.0,    # average launch (full layers and the last layer's)
                           "source": "profiles/pmc_traffic_bench_cfg5_3b_ragged128.md"},
-    "cfg3_1b_ragged64": {"bytes": (354061.6 * 2.0 + 84440.0 * 1.0) * 1024.0,       # a full layer (5144 rows)
+    "cfg3_1b_ragged64": {"bytes": (338432.4 * 2.0 + 82304.0 * 1.0) * 1024.0,       # a full layer (5144 rows)
                          "source": "profiles/pmc_traffic_gemm_gate_up_cfg3.md"},
     # ctc_gate at saturation size, both kernels of a call (scores read once; entropies and labels written, then read back)
     "gate_saturation_V512_bfloat16": {"bytes": ((781270.2 + 6478.5) * 2.0 + 12228.8 + 400.6) * 1024.0,

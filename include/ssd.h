@@ -224,12 +224,13 @@ int ctc_head_gate(ssd_ctx *ctx, const void *enc_h, const int32_t *cu_frames /*ho
  *   w_k, w_v dev [d_h, d_enc] bf16   key and value projections of the frames
  *   w_o dev [d_out, d_h] bf16        output projection (d_out = d_model of the LLM)
  * n_heads heads of d_h / n_heads dims, scores scaled by 1 / sqrt(d_head).  Limits: n_q <= 4, n_q * n_heads <= 64,
- * window <= 32, d_h a multiple of 64 and of n_heads, d_enc of 64, d_out of 256 (SSD_ESHAPE otherwise).
+ * window <= 32, d_h a multiple of 64 and of 4 * n_heads, d_enc of 64, d_out of 256 (SSD_ESHAPE otherwise).
  * The key projection is folded into n_q * n_heads score rows at this point (the queries are constants).
  *
  * qformer_pool: for every utterance b and window w of its frames (the last one may be shorter and attends over
  * the frames it has), query j: p = softmax over the window's frames of the head-wise scores, o = sum_t p_t w_v h_t,
- * g = w_o o, written as bf16 to speech_emb row cu_speech[b] + n_q * w + j; cu_speech (host, B + 1 entries) is
+ * g = w_o o, written as bf16 to speech_emb row cu_speech[b] + n_q * w + j (the projected values w_v h_t pass through
+ * IEEE half on the way: one beyond 65504 is clamped and raises SSD_FLAG_ACT_OVERFLOW); cu_speech (host, B + 1 entries) is
  * filled with the prefix sums S_b = n_q * ceil(T_b / window) that verify_forward takes.  The rest of a q-former
  * layer (self-attention among the queries, feed-forward block, normalisation, second layer) is not described in
  * the paper and not part of this call.

@@ -187,13 +187,14 @@ HeadPlan plan_head(int64_t frames, int64_t utts, int V) {
     return p;
 }
 
-struct QformerPlan { size_t wins, kv, o, total; int64_t max_windows; };
+struct QformerPlan { size_t wins, scores, vals, o, total; int64_t max_windows; };
 QformerPlan plan_qformer(int64_t frames, int64_t utts, int window, int n_q, int d_h) {
     QformerPlan p;
     p.max_windows = frames / window + utts;                  // every utterance may end in a short window
     size_t o = 0;
     p.wins = o; o = align_up(o + (size_t)p.max_windows * sizeof(QWindow));
-    p.kv = o; o = align_up(o + (size_t)frames * qformer_cat_rows(d_h) * 4);
+    p.scores = o; o = align_up(o + (size_t)frames * QF_SCORE_COLS * 4);
+    p.vals = o; o = align_up(o + (size_t)frames * d_h * 2);
     p.o = o; o = align_up(o + (size_t)p.max_windows * n_q * d_h * 2);
     p.total = o;
     return p;
@@ -745,8 +746,8 @@ int ssd_set_qformer(ssd_ctx* ctx, const void* q_proj, const void* w_k, const voi
     if (n_q > QF_MAX_QUERIES || n_q * n_heads > QF_SCORE_COLS || window > QF_MAX_WINDOW)
         return fail(ctx, SSD_ESHAPE, "ssd_set_qformer: at most %d queries, %d (query, head) pairs and windows of %d frames",
                     QF_MAX_QUERIES, QF_SCORE_COLS, QF_MAX_WINDOW);
-    if (d_h % n_heads || d_h % 64 || d_enc % 64 || d_out % 256)
-        return fail(ctx, SSD_ESHAPE, "ssd_set_qformer: d_h must be a multiple of n_heads and of 64, d_enc of 64, d_out of 256");
+    if (d_h % n_heads || (d_h / n_heads) % 4 || d_h % 64 || d_enc % 64 || d_out % 256)
+        return fail(ctx, SSD_ESHAPE, "ssd_set_qformer: d_h must be a multiple of 4 * n_heads and of 64, d_enc of 64, d_out of 256");
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     auto drop = [&](void* p) {
         if (!p) return;
@@ -796,13 +797,15 @@ int qformer_pool(ssd_ctx* ctx, const void* enc_h, const int32_t* cu_frames, int 
     char* ws = static_cast<char*>(ctx->ws);
     int rc = upload(ctx, wins.data(), ws + p.wins, wins.size() * sizeof(QWindow));
     if (rc != SSD_OK) return rc;
-    float* kv = reinterpret_cast<float*>(ws + p.kv);
+    float* scores = reinterpret_cast<float*>(ws + p.scores);
+    uint16_t* vals = reinterpret_cast<uint16_t*>(ws + p.vals);
     uint16_t* o = reinterpret_cast<uint16_t*>(ws + p.o);
     const int n_cat = qformer_cat_rows(d_h);
     {
         ProfScope ps(ctx, SSD_PROF_QFORMER);
-        launch_gemm_store_f32(static_cast<const uint16_t*>(enc_h), ctx->qf_wcat, kv, (int)n_rows, n_cat, d_enc, true, ctx->stream);
-        launch_qformer_pool(kv, n_cat, reinterpret_cast<const QWindow*>(ws + p.wins), n_windows, n_q, ctx->qf_heads, d_h, o, ctx->stream);
+        launch_gemm_scores_values(static_cast<const uint16_t*>(enc_h), ctx->qf_wcat, scores, vals, (int)n_rows, n_cat, d_enc, d_h,
+                                  ctx->dev_flags, true, ctx->stream);
+        launch_qformer_pool(scores, vals, reinterpret_cast<const QWindow*>(ws + p.wins), n_windows, n_q, ctx->qf_heads, d_h, o, ctx->stream);
         launch_gemm_store_16(o, ctx->qf_wo, static_cast<uint16_t*>(speech_emb), n_windows * n_q, ctx->qf_dout, d_h, true, ctx->stream);
     }
     HIP_TRY(ctx, hipGetLastError());

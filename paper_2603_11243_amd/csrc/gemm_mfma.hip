@@ -421,36 +421,50 @@ struct EpiPartial {
     }
 };
 
-// Plain stores for products outside the decoder layer (the projector's windowed cross-attention): the
-// accumulator as fp32, or rounded to the operand type, into rows of ldc elements.
+// Epilogues for products outside the decoder layer (the projector's windowed cross-attention).
+// EpiScoresValues: the product [frames, 64 score columns | d_h value columns | padding] is split on the way out.
+// The score columns stay fp32 (they go through an exponential), rows of 64; the value columns are rounded to IEEE
+// half (2^-12 relative, an eighth of the bf16 rounding their weighted sums get afterwards; beyond 65504 they
+// saturate and SSD_FLAG_ACT_OVERFLOW is raised), rows of d_h: 2.3 KB per frame instead of 5 KB of fp32.
 template <bool BF_>
-struct EpiStoreF32 {
+struct EpiScoresValues {
     static constexpr bool WANTS_SPLIT = false, BF = BF_, TRANSPOSE = true, USES_LDS = false;
-    float* c; int ldc;
+    float* scores; uint16_t* vals; int d_h; int32_t* flags;
     template <int TM, int TN, class L = Layout32>
     __device__ __forceinline__ void operator()(typename L::vec_t (&acc)[TM][TN], int row0, int col0, int M, int lane) const {
+        bool bad = false;
         if constexpr (L::TRANSPOSED) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = row0 + L::row(i, lane);
                 if (row >= M) continue;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    *reinterpret_cast<float4*>(c + (int64_t)row * ldc + col0 + L::col4(j, lane)) =
-                        make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                for (int j = 0; j < TN; ++j) {
+                    const int col = col0 + L::col4(j, lane);           // blocks of 16 columns never straddle column 64
+                    if (col < QF_SCORE_COLS)
+                        *reinterpret_cast<float4*>(scores + (int64_t)row * QF_SCORE_COLS + col) =
+                            make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                    else if (col - QF_SCORE_COLS < d_h)
+                        *reinterpret_cast<uint2*>(vals + (int64_t)row * d_h + (col - QF_SCORE_COLS)) =
+                            make_uint2(pack_f16x2_sat(acc[i][j][0], acc[i][j][1], bad), pack_f16x2_sat(acc[i][j][2], acc[i][j][3], bad));
+                }
             }
-            return;
         } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < L::REGS; ++r) {
-                const int row = row0 + L::row(i, r, lane);
-                if (row >= M) continue;
+                for (int r = 0; r < L::REGS; ++r) {
+                    const int row = row0 + L::row(i, r, lane);
+                    if (row >= M) continue;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) c[(int64_t)row * ldc + col0 + L::col(j, lane)] = acc[i][j][r];
-            }
+                    for (int j = 0; j < TN; ++j) {
+                        const int col = col0 + L::col(j, lane);
+                        if (col < QF_SCORE_COLS) scores[(int64_t)row * QF_SCORE_COLS + col] = acc[i][j][r];
+                        else if (col - QF_SCORE_COLS < d_h) vals[(int64_t)row * d_h + (col - QF_SCORE_COLS)] = f32_to_f16_sat(acc[i][j][r], bad);
+                    }
+                }
         }
+        if (bad) raise_flag(flags, SSD_FLAG_ACT_OVERFLOW);
     }
 };
 template <bool BF_>
@@ -725,9 +739,10 @@ int launch_gemm_residual(const uint16_t* A, const uint16_t* W, const void* W_str
                     : gemm_residual_impl<false>(A, W, W_stream, x, partials, M, N, K, descale, st);
 }
 
-void launch_gemm_store_f32(const uint16_t* A, const uint16_t* W, float* C, int M, int N, int K, bool bf16_ops, hipStream_t st) {
-    if (bf16_ops) launch_by_shape(A, W, nullptr, M, N, K, EpiStoreF32<true>{C, N}, st);
-    else launch_by_shape(A, W, nullptr, M, N, K, EpiStoreF32<false>{C, N}, st);
+void launch_gemm_scores_values(const uint16_t* A, const uint16_t* W, float* scores, uint16_t* vals, int M, int N, int K, int d_h,
+                               int32_t* flags, bool bf16_ops, hipStream_t st) {
+    if (bf16_ops) launch_by_shape(A, W, nullptr, M, N, K, EpiScoresValues<true>{scores, vals, d_h, flags}, st);
+    else launch_by_shape(A, W, nullptr, M, N, K, EpiScoresValues<false>{scores, vals, d_h, flags}, st);
 }
 void launch_gemm_store_16(const uint16_t* A, const uint16_t* W, uint16_t* C, int M, int N, int K, bool bf16_ops, hipStream_t st) {
     if (bf16_ops) launch_by_shape(A, W, nullptr, M, N, K, EpiStore16<true>{C, N}, st);

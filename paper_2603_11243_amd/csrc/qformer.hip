@@ -6,7 +6,8 @@
 //     q_proj[j, h] . (w_k h_t)[h] / sqrt(d_head)  =  (w_k[h]^T q_proj[j, h] / sqrt(d_head)) . h_t,
 // is a fixed linear function of the frame: the key projection folds into n_q * n_heads score rows.  Those rows and
 // w_v form one weight matrix, and the path is
-//   1. kv [frames, 64 + d_h] = enc_h w_cat^T             one MFMA GEMM (gemm_mfma.hip), fp32 out
+//   1. [scores | values] = enc_h w_cat^T                  one MFMA GEMM (gemm_mfma.hip): scores [frames, 64] fp32,
+//                                                         values [frames, d_h] IEEE half
 //   2. per window: softmax over its frames of each score column, weighted sum of the value columns   (here)
 //   3. g [3 windows, d_out] = o w_o^T                      one MFMA GEMM, stored in the storage type of speech_emb
 // Windows never cross an utterance; the last window of an utterance may hold fewer frames.
@@ -47,19 +48,18 @@ void launch_qformer_fold(const uint16_t* q_proj, const uint16_t* w_k, const uint
 }
 
 // One workgroup per window.  Scores of the window's frames go through LDS, one thread normalises one
-// (query, head) column over the frames, then every thread owns value columns c, c + 256, ... and accumulates
-// the n_q weighted sums of its column over the frames (coalesced rows of kv).
+// (query, head) column over the frames, then every thread owns four consecutive value columns (one 8-byte load
+// per frame, whole rows coalesced) and accumulates their n_q weighted sums over the frames.
 template <int NQ>
-__global__ void __launch_bounds__(256) qformer_pool_kernel(const float* __restrict__ kv, int ldkv, const QWindow* __restrict__ wins,
-                                                           int n_heads, int d_h, bf16_t* __restrict__ o) {
+__global__ void __launch_bounds__(256) qformer_pool_kernel(const float* __restrict__ scores, const f16_t* __restrict__ vals,
+                                                           const QWindow* __restrict__ wins, int n_heads, int d_h,
+                                                           bf16_t* __restrict__ o) {
     __shared__ float p_s[QF_SCORE_COLS][QF_MAX_WINDOW + 1];
     const QWindow w = wins[blockIdx.x];
     const int n_pairs = NQ * n_heads;
-    const float* base = kv + (int64_t)w.frame0 * ldkv;
-    for (int i = threadIdx.x; i < w.n_frames * QF_SCORE_COLS; i += 256) {
-        const int t = i / QF_SCORE_COLS, pair = i % QF_SCORE_COLS;            // a frame's 64 score columns are contiguous
-        p_s[pair][t] = base[(int64_t)t * ldkv + pair];
-    }
+    const float* sbase = scores + (int64_t)w.frame0 * QF_SCORE_COLS;
+    for (int i = threadIdx.x; i < w.n_frames * QF_SCORE_COLS; i += 256)        // the window's scores are one contiguous piece
+        p_s[i % QF_SCORE_COLS][i / QF_SCORE_COLS] = sbase[i];
     __syncthreads();
     if (threadIdx.x < n_pairs) {
         float* p = p_s[threadIdx.x];
@@ -71,26 +71,37 @@ __global__ void __launch_bounds__(256) qformer_pool_kernel(const float* __restri
         for (int t = 0; t < w.n_frames; ++t) p[t] *= inv;
     }
     __syncthreads();
-    const int dh = d_h / n_heads;
-    for (int c = threadIdx.x; c < d_h; c += 256) {
+    const int dh = d_h / n_heads;                                              // a multiple of 4: four columns share a head
+    const f16_t* vbase = vals + (int64_t)w.frame0 * d_h;
+    for (int c = 4 * threadIdx.x; c < d_h; c += 1024) {
         const int h = c / dh;
-        float acc[NQ];
+        float acc[NQ][4];
 #pragma unroll
-        for (int j = 0; j < NQ; ++j) acc[j] = 0.f;
+        for (int j = 0; j < NQ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
         for (int t = 0; t < w.n_frames; ++t) {
-            const float v = base[(int64_t)t * ldkv + QF_SCORE_COLS + c];
+            const uint2 raw = *reinterpret_cast<const uint2*>(vbase + (int64_t)t * d_h + c);
+            const float v[4] = {f16_to_f32((f16_t)(raw.x & 0xffffu)), f16_to_f32((f16_t)(raw.x >> 16)),
+                                f16_to_f32((f16_t)(raw.y & 0xffffu)), f16_to_f32((f16_t)(raw.y >> 16))};
 #pragma unroll
-            for (int j = 0; j < NQ; ++j) acc[j] = fmaf(p_s[j * n_heads + h][t], v, acc[j]);
+            for (int j = 0; j < NQ; ++j) {
+                const float p = p_s[j * n_heads + h][t];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(p, v[e], acc[j][e]);
+            }
         }
 #pragma unroll
-        for (int j = 0; j < NQ; ++j) o[((int64_t)blockIdx.x * NQ + j) * d_h + c] = f32_to_bf16(acc[j]);
+        for (int j = 0; j < NQ; ++j)
+            *reinterpret_cast<uint2*>(o + ((int64_t)blockIdx.x * NQ + j) * d_h + c) =
+                make_uint2(pack_bf16x2(acc[j][0], acc[j][1]), pack_bf16x2(acc[j][2], acc[j][3]));
     }
 }
 
-void launch_qformer_pool(const float* kv, int ldkv, const QWindow* wins, int n_windows, int n_q, int n_heads, int d_h,
-                         uint16_t* o, hipStream_t st) {
+void launch_qformer_pool(const float* scores, const uint16_t* vals, const QWindow* wins, int n_windows, int n_q, int n_heads,
+                         int d_h, uint16_t* o, hipStream_t st) {
     if (n_windows <= 0) return;
-#define SSD_QF(NQ) hipLaunchKernelGGL(qformer_pool_kernel<NQ>, dim3(n_windows), dim3(256), 0, st, kv, ldkv, wins, n_heads, d_h, o)
+#define SSD_QF(NQ) hipLaunchKernelGGL(qformer_pool_kernel<NQ>, dim3(n_windows), dim3(256), 0, st, scores, vals, wins, n_heads, d_h, o)
     if (n_q == 1) SSD_QF(1); else if (n_q == 2) SSD_QF(2); else if (n_q == 3) SSD_QF(3); else SSD_QF(4);
 #undef SSD_QF
 }

@@ -40,10 +40,10 @@ int qformer_cat_rows(int d_h);       // rows of the fused [scores | values] weig
 // rows 64 .. 64 + d_h - 1 hold w_v, the rest is zero
 void launch_qformer_fold(const uint16_t* q_proj, const uint16_t* w_k, const uint16_t* w_v, int n_q, int n_heads, int d_h,
                          int d_enc, uint16_t* w_cat, hipStream_t st);
-// kv [frames, ldkv] fp32 = enc_h w_cat^T; for every window: softmax of its score columns over its frames, then the
-// weighted sum of its value columns: o [n_windows * n_q, d_h] bf16
-void launch_qformer_pool(const float* kv, int ldkv, const QWindow* wins, int n_windows, int n_q, int n_heads, int d_h,
-                         uint16_t* o, hipStream_t st);
+// scores [frames, 64] fp32 and vals [frames, d_h] IEEE half = enc_h w_cat^T; for every window: softmax of its score
+// columns over its frames, then the weighted sum of its value columns: o [n_windows * n_q, d_h] bf16
+void launch_qformer_pool(const float* scores, const uint16_t* vals, const QWindow* wins, int n_windows, int n_q, int n_heads,
+                         int d_h, uint16_t* o, hipStream_t st);
 
 // ---- row metadata built on the host for one verify_forward call
 // src code of a decoder row: speech rows hold the speech_emb row index; token rows hold
@@ -109,7 +109,9 @@ void launch_gemm_swiglu(const uint16_t* A, const uint16_t* Wgu_packed, const voi
                         float descale, int32_t* flags, bool bf16_ops, hipStream_t st);
 // plain products C[M,N] = A[M,K] W[N,K]^T with fp32 accumulation, stored as fp32 or rounded to the operand type
 // (N % 256 == 0, K % 64 == 0, row-major 16-bit operands of the type bf16_ops selects)
-void launch_gemm_store_f32(const uint16_t* A, const uint16_t* W, float* C, int M, int N, int K, bool bf16_ops, hipStream_t st);
+// C = A W^T with W = [64 score rows | d_h value rows | zero rows up to N]: scores [M, 64] fp32, vals [M, d_h] IEEE half (saturating)
+void launch_gemm_scores_values(const uint16_t* A, const uint16_t* W, float* scores, uint16_t* vals, int M, int N, int K, int d_h,
+                               int32_t* flags, bool bf16_ops, hipStream_t st);
 void launch_gemm_store_16(const uint16_t* A, const uint16_t* W, uint16_t* C, int M, int N, int K, bool bf16_ops, hipStream_t st);
 // second copy of an f16 weight matrix W[N,K] for the few-row kernel (N % 64 == 0, K % 256 == 0)
 bool stream_layout_supported(int N, int K);
