@@ -95,8 +95,11 @@ struct GemmTile {
                                                f32x16_t (&acc)[TM][TN], int n_rows_w = 0x7fffffff, int lda = 0, int ldw = 0) {
         if (lda == 0) lda = K;                               // row strides in elements (default: dense rows)
         if (ldw == 0) ldw = K;
+        // Wavefronts beyond WAVES form further groups of WAVES that run the same tile on their own smem and K range
+        // (in-workgroup K split: the caller adds the groups' accumulators); every group must run the same number
+        // of slices, since the barriers below are workgroup barriers.
         const int tid = threadIdx.x, lane = tid % 64;
-        const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+        const int wave = __builtin_amdgcn_readfirstlane((tid / 64) % WAVES);
         const int wm = wave / WAVES_N, wn = wave % WAVES_N;
         const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A), w_rsrc = make_rsrc(W);
 

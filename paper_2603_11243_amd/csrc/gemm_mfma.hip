@@ -540,6 +540,71 @@ static void launch_gemm(const f16_t* A, const f16_t* W, int M, int N, int K, int
     hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(64 * WAVES_M * WAVES_N), lds, st, A, W, M, N, K, splits, epi);
 }
 
+// One-wavefront tile with the K range split over KG wavefronts of the workgroup, each with its own LDS ring; the
+// partial accumulators are added through LDS in group order (deterministic) and group 0 runs the epilogue.  For
+// projections with few rows, few column tiles and an epilogue that needs whole sums (QKV + RoPE at 33-128 rows): a
+// CU then keeps KG rings of weight and activation slices in flight instead of one.
+template <int BM, int BN, int NSTAGE, int KG, class Epi>
+__global__ void __launch_bounds__(64 * KG)
+gemm_mfma_kgroups_kernel(const f16_t* __restrict__ A, const f16_t* __restrict__ W, int M, int N, int K, Epi epi) {
+    using Tile = GemmTile<BM, BN, 1, 1, NSTAGE, Epi::BF>;
+    constexpr int RING = (int)gemm_lds_bytes<BM, BN, NSTAGE>();
+    constexpr int ACC_FLOATS = Tile::TM * Tile::TN * 16;               // per lane
+    static_assert(ACC_FLOATS * 64 * 4 <= RING, "a group's partial tile must fit its ring");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    const int g = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
+    const int per = K / GEMM_BK / KG;                                   // the launcher checks divisibility
+    f32x16_t acc[Tile::TM][Tile::TN];
+#pragma unroll
+    for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    Tile::run(A, W, M, K, tm * BM, tn * BN, g * per, (g + 1) * per, smem_raw + g * RING, acc);
+    // a group's ring is read by that group only and all its reads have completed: it may hold the partial tile
+    float* mine = reinterpret_cast<float*>(smem_raw + g * RING);
+    if (g > 0) {
+#pragma unroll
+        for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * Tile::TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (g == 0) {
+        for (int o = 1; o < KG; ++o) {
+            const float* theirs = reinterpret_cast<const float*>(smem_raw + o * RING);
+#pragma unroll
+            for (int i = 0; i < Tile::TM; ++i)
+#pragma unroll
+                for (int j = 0; j < Tile::TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += theirs[((i * Tile::TN + j) * 16 + r) * 64 + lane];
+        }
+        epi.template operator()<Tile::TM, Tile::TN>(acc, tm * BM, tn * BN, M, lane);
+    }
+}
+
+template <int BM, int BN, int NSTAGE, int KG, class Epi>
+static void launch_gemm_kgroups(const f16_t* A, const f16_t* W, int M, int N, int K, const Epi& epi, hipStream_t st) {
+    if (M <= 0) return;
+    auto kern = gemm_mfma_kgroups_kernel<BM, BN, NSTAGE, KG, Epi>;
+    constexpr size_t lds = KG * gemm_lds_bytes<BM, BN, NSTAGE>();
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    const int tiles = ((M + BM - 1) / BM) * (N / BN);
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * KG), lds, st, A, W, M, N, K, epi);
+}
+
 // Big tiles on v_mfma_f32_16x16x32_f16 (gemm_core16.h): same tile shapes, workgroup order and epilogues.
 template <int BM, int BN, int WAVES_M, int WAVES_N, class Epi>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
@@ -647,6 +712,13 @@ static void launch_skinny(const f16_t* A, const f16_t* W, const void* Ws, int M,
     // split (QKV: 64-80 tiles) is cut into row tiles of 32 or 64 as well; the row tiles of a column slab then
     // read the same weights, which the L2 serves.
     const int col_tiles = (N / 64) * splits;
+    if constexpr (!Epi::WANTS_SPLIT) {
+        // whole sums wanted (no K split across workgroups) and few column tiles: split K inside the workgroup
+        if (col_tiles <= 96 && M > 32 && (K / GEMM_BK) % 4 == 0 && K / GEMM_BK >= 16) {
+            launch_gemm_kgroups<32, 64, 3, 4>(A, W, M, N, K, epi, st);
+            return;
+        }
+    }
     if (M <= 32 || (col_tiles <= 96 && M > 32)) launch_gemm<32, 64, 1, 1, 6>(A, W, M, N, K, splits, epi, st);
     else if (col_tiles <= 160 && M > 64) launch_gemm<64, 64, 2, 1, 6>(A, W, M, N, K, splits, epi, st);
     else launch_gemm<128, 64, 4, 1, 6>(A, W, M, N, K, splits, epi, st);
