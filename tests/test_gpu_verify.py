@@ -258,6 +258,30 @@ def test_accept_prefix_alone_row_counts_around_lm_head_tiles(Mv):
         check_accept_len(res["accept_len"][b], res["all_accepted"][b], lp[cu_d[b]:cu_d[b + 1]], tau, tol)
 
 
+@pytest.mark.parametrize("name", ["cfg3_1b_ragged64", "cfg5_3b_ragged128"])
+def test_bf16_utterance_lengths_around_key_blocks(name):
+    """One layer of the 1B-width (2 query heads per KV head) and of the 3B-width decoder (3 per KV head); utterance
+    lengths on and next to the attention kernel's 64-key blocks and 32-row wavefronts, nearly every position a
+    verification row: a block that ends exactly at the utterance's end is loaded whole, any other last block row by
+    row with clamping, and the last utterance of the batch ends where the buffer ends."""
+    from workloads.synth import VerifyInputs
+    wl = scaled_down(WORKLOADS[name], n_layers=1, B=9)
+    w = make_model_weights(wl.model, 77, device="cuda")
+    rng = np.random.default_rng(5)
+    n = [64, 1 + 2, 63, 65, 128, 127, 129, 33, 192]
+    S, P = [1] * 9, [1] * 9
+    U = [k - 2 for k in n]
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    sp = (torch.randn(sum(S), wl.model.d_model, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    vi = VerifyInputs(sp, cu(S), rng.integers(0, wl.model.vocab, sum(P)).astype(np.int32), cu(P),
+                      rng.integers(0, wl.model.vocab, sum(U)).astype(np.int32), cu(U))
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    worst = _compare(wl, w, vi, res, tau)
+    assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a wrong key block would be O(1)
+
+
 def test_bf16_empty_drafts_and_single_row_utterances():
     """bf16 path, two 1B-width layers: utterances without a draft inside a batch (vacuous acceptance), an
     utterance made of one speech row, and a batch in which nobody has a draft (nothing to score)."""
