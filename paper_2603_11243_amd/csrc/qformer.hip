@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(256) qformer_pool_kernel(const float* __restri
     for (int i = threadIdx.x; i < w.n_frames * QF_SCORE_COLS; i += 256)        // the window's scores are one contiguous piece
         p_s[i % QF_SCORE_COLS][i / QF_SCORE_COLS] = sbase[i];
     __syncthreads();
-    if (threadIdx.x < n_pairs) {
+    if ((int)threadIdx.x < n_pairs) {
         float* p = p_s[threadIdx.x];
         float m = -INFINITY;
         for (int t = 0; t < w.n_frames; ++t) m = fmaxf(m, p[t]);

@@ -1,6 +1,5 @@
 """The two-phase schedule of Sec. 3.2 (token-budget bins, verification and fallback batched separately, acoustic
 embeddings parked in pinned host memory between the passes) against the single-batch run and the oracle."""
-from dataclasses import replace
 
 import numpy as np
 import pytest

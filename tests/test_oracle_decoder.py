@@ -9,7 +9,6 @@ import os
 from dataclasses import replace
 
 import numpy as np
-import pytest
 import torch
 import torch.nn.functional as F
 

@@ -4,7 +4,7 @@ The paper evaluates on public speech corpora that are not available here; these
 records only fix tensor shapes, length mixes and gate rates.  Rates: 25 CTC
 frames per second of audio, 6 speech embeddings per second.
 """
-from dataclasses import dataclass, field, replace
+from dataclasses import dataclass, replace
 from typing import Tuple
 
 
