@@ -97,7 +97,13 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(float* __restrict__ x, con
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int i = lane + 64 * j;
-        v[j] = i < n4 ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < n4) {
+            typedef float f32x4v __attribute__((ext_vector_type(4)));
+            const f32x4v t = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(src) + i);
+            v[j] = make_float4(t[0], t[1], t[2], t[3]);
+        } else {
+            v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
     if (n_splits > 1) {
         // pending K-split partial sums of the projection before this norm: add them in split order
