@@ -138,7 +138,9 @@ struct EpiResidualLds {
 #pragma unroll
             for (int it = 0; it < NI; ++it) {
                 const int row = min(row0 + half * ROWS + 4 * it + rr, M - 1);
-                old[it] = *reinterpret_cast<const float4*>(x + (int64_t)row * ldx + col0 + cc);
+                typedef float f32x4v __attribute__((ext_vector_type(4)));
+                const f32x4v t = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(x + (int64_t)row * ldx + col0 + cc));
+                old[it] = make_float4(t[0], t[1], t[2], t[3]);
             }
             if (half) __builtin_amdgcn_wave_barrier();       // the reads of the first half are done (waited for below)
 #pragma unroll
