@@ -282,6 +282,32 @@ def test_bf16_utterance_lengths_around_key_blocks(name):
     assert worst < 5e-3           # one layer: far inside the 2e-2 budget, a wrong key block would be O(1)
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16])
+def test_bf16_random_ragged_batches(seed):
+    """Seeded random ragged batches through one decoder layer (1B width for even seeds, 3B width for odd ones): 1 to 12
+    utterances with 1 to 300 speech rows, 0 to 20 prompt tokens and 0 to 120 draft tokens each, so that total row
+    counts, utterance lengths, key-block counts and verification-row counts fall on no particular boundary."""
+    from workloads.synth import VerifyInputs
+    rng = np.random.default_rng(seed)
+    B = int(rng.integers(1, 13))
+    wl = scaled_down(WORKLOADS["cfg5_3b_ragged128" if seed % 2 else "cfg3_1b_ragged64"], n_layers=1, B=B)
+    w = make_model_weights(wl.model, 1000 + seed, device="cuda")
+    S = rng.integers(1, 301, B).tolist()
+    P = rng.integers(0, 21, B).tolist()
+    U = rng.integers(0, 121, B).tolist()
+    if sum(U) == 0:
+        U[0] = 5
+    cu = lambda a: np.concatenate([[0], np.cumsum(a)]).astype(np.int32)
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    sp = (torch.randn(sum(S), wl.model.d_model, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    vi = VerifyInputs(sp, cu(S), rng.integers(0, wl.model.vocab, sum(P)).astype(np.int32), cu(P),
+                      rng.integers(0, wl.model.vocab, sum(U)).astype(np.int32), cu(U))
+    tau = _tau_for(wl)
+    res = _run_gpu(wl, w, vi, tau)
+    worst = _compare(wl, w, vi, res, tau)
+    assert worst < 5e-3           # one layer: far inside the 2e-2 budget
+
+
 def test_bf16_empty_drafts_and_single_row_utterances():
     """bf16 path, two 1B-width layers: utterances without a draft inside a batch (vacuous acceptance), an
     utterance made of one speech row, and a batch in which nobody has a draft (nothing to score)."""
