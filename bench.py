@@ -39,7 +39,7 @@ LEGS = ["main", "cpu_baseline", "mfma_ceiling", "hbm_ceiling", "ar_fallback", "g
 # of the kernel on M rows), each scaled by what the same counter reads for a plain 1 GiB device copy
 # (`--copy-reference`).  Every entry names the committed summary it was read from.
 MEASURED_TRAFFIC = {
-    "cfg5_3b_ragged128": {"bytes": (1082106.8 * 2.0 + 238757.9 * 1.0) * 1024.0,    # average launch (full layers and the last layer's)
+    "cfg5_3b_ragged128": {"bytes": (1082288.8 * 2.0 + 238764.1 * 1.0) * 1024.0,    # average launch (full layers and the last layer's)
                           "source": "profiles/pmc_traffic_bench_cfg5_3b_ragged128.md"},
     "cfg3_1b_ragged64": {"bytes": (338432.4 * 2.0 + 82304.0 * 1.0) * 1024.0,       # a full layer (5144 rows)
                          "source": "profiles/pmc_traffic_gemm_gate_up_cfg3.md"},
